@@ -1,0 +1,463 @@
+"""Pins for the CPU oracle: everything here checks `oracle/` against something
+other than itself - hand-worked fixtures, brute force, closed forms, invariants
+of the definition, and library routines (numpy / torch CPU).  No GPU needed.
+
+Citations: Comp / Recovery of Algorithm 1 (Sec. IV-B), Eq. (6), batched-write
+semantics (Sec. IV-C), Snapshot / "Merge in CPU" of Algorithm 2 (Sec. VI-B),
+Eq. (4), rho of Sec. VII-A, fidelity of Exp. 6 (Table VI).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_04084_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+def assert_bits_equal(a, b):
+    np.testing.assert_array_equal(bits(a), bits(b))
+
+
+def _floats(line):
+    return np.array([float(x) for x in line.split()[1:]], dtype=np.float32)
+
+
+def _ints(line):
+    return np.array([int(x) for x in line.split()[1:]], dtype=np.int64)
+
+
+def _read(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return [ln.strip() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# ---------------------------------------------------------------- top-k + EF
+
+def brute_force_topk(a, k):
+    """Repeated arg-max under (|a| desc by bit pattern, index asc); pure Python."""
+    keys = [int(x) & 0x7FFFFFFF for x in bits(a)]
+    taken = [False] * len(keys)
+    sel = []
+    for _ in range(k):
+        best = -1
+        for i, ki in enumerate(keys):
+            if taken[i]:
+                continue
+            if best < 0 or ki > keys[best]:  # strict: earlier index wins ties
+                best = i
+        taken[best] = True
+        sel.append(best)
+    return sorted(sel)
+
+
+def test_golden_topk_worked_example():
+    L = {ln.split()[0]: ln for ln in _read("topk_ef_worked.txt")}
+    idx, val, r_new = oracle.topk_ef(_floats(L["g"]), _floats(L["r"]), _ints(L["seg_off"]),
+                                     _ints(L["seg_k"]))
+    np.testing.assert_array_equal(idx, _ints(L["idx"]))
+    assert_bits_equal(val, _floats(L["val"]))
+    assert_bits_equal(r_new, _floats(L["r_new"]))
+    idx2, val2, r2 = oracle.topk_ef(_floats(L["g"]), _floats(L["r"]), _ints(L["seg_off"]),
+                                    _ints(L["seg_k"]), select=True)
+    np.testing.assert_array_equal(idx2, idx)
+    assert_bits_equal(val2, val)
+    assert_bits_equal(r2, r_new)
+
+
+@pytest.mark.parametrize("n", [1, 2, 7, 64, 257])
+def test_topk_brute_force_all_k(n):
+    rs = np.random.RandomState(n)
+    # quantised values -> many exact ties, signs mixed
+    g = (np.round(rs.standard_normal(n) * 3) / 4).astype(np.float32)
+    r = (np.round(rs.standard_normal(n) * 2) / 8).astype(np.float32)
+    a = (r + g).astype(np.float32)
+    ks = range(0, n + 1) if n <= 64 else [0, 1, 2, n // 3, n - 1, n]
+    for k in ks:
+        idx, val, r_new = oracle.topk_ef(g, r, [0, n], [k])
+        want = brute_force_topk(a, k)
+        assert idx.tolist() == want, (n, k)
+        assert_bits_equal(val, a[want])
+        exp_r = a.copy()
+        exp_r[want] = 0.0
+        assert_bits_equal(r_new, exp_r)
+
+
+def test_topk_brute_force_medium_random():
+    n, rs = 4096, np.random.RandomState(5)
+    g = rs.standard_normal(n).astype(np.float32)
+    r = (rs.standard_normal(n) * 0.3).astype(np.float32)
+    a = (r + g).astype(np.float32)
+    for k in (1, 41, 400):
+        idx, _, _ = oracle.topk_ef(g, r, [0, n], [k])
+        assert idx.tolist() == brute_force_topk(a, k)
+
+
+def test_accumulate_is_one_fp32_add():
+    rs = np.random.RandomState(11)
+    n = 10000
+    g = (rs.standard_normal(n) * 10.0 ** rs.uniform(-8, 8, n)).astype(np.float32)
+    r = (rs.standard_normal(n) * 10.0 ** rs.uniform(-8, 8, n)).astype(np.float32)
+    _, _, r_new = oracle.topk_ef(g, r, [0, n], [0])  # nothing selected: r_new == a
+    assert_bits_equal(r_new, g + r)  # numpy float32 add is a single IEEE add
+    # and it is NOT the double-rounded or float64 sum in general
+    assert np.any(r_new.astype(np.float64) != g.astype(np.float64) + r.astype(np.float64))
+
+
+def test_residual_plus_selected_equals_accumulated():
+    wl = synth.workload("flat1m")
+    rs = np.random.RandomState(3)
+    n = 50000
+    g = rs.standard_normal(n).astype(np.float32)
+    r = (rs.standard_normal(n) * 0.5).astype(np.float32)
+    seg_off = [0, 1000, 1001, 30000, n]
+    seg_k = synth.seg_topk(np.diff(seg_off), *wl.rho)
+    idx, val, r_new = oracle.topk_ef(g, r, seg_off, seg_k)
+    a = g + r
+    scat = np.zeros(n, dtype=np.float32)
+    scat[idx] = val
+    np.testing.assert_array_equal(r_new + scat, a)            # numeric ==
+    assert_bits_equal(val, a[idx])                            # values bit for bit
+    assert np.all(bits(r_new[idx]) == 0)                      # selected -> +0.0
+    keep = np.ones(n, bool)
+    keep[idx] = False
+    assert_bits_equal(r_new[keep], a[keep])                   # untouched elsewhere
+    assert np.all(np.diff(idx) > 0)                           # strictly ascending
+    assert idx.shape[0] == int(seg_k.sum())
+
+
+def test_boundary_and_tie_rule():
+    rs = np.random.RandomState(9)
+    n = 20000
+    g = (np.round(rs.standard_normal(n) * 8) / 8).astype(np.float32)  # many ties
+    for k in (1, 100, 777, 5000):
+        idx, _, _ = oracle.topk_ef(g, np.zeros(n, np.float32), [0, n], [k])
+        key = bits(g) & 0x7FFFFFFF
+        sel = np.zeros(n, bool)
+        sel[idx] = True
+        kmin = key[sel].min()
+        assert kmin >= key[~sel].max()
+        tie_sel = np.nonzero(sel & (key == kmin))[0]
+        tie_uns = np.nonzero(~sel & (key == kmin))[0]
+        if len(tie_uns) and len(tie_sel):
+            assert tie_sel.max() < tie_uns.min()
+
+
+def test_special_cases_k_equals_n_and_k_equals_one():
+    rs = np.random.RandomState(2)
+    n = 1000
+    g = rs.standard_normal(n).astype(np.float32)
+    r = rs.standard_normal(n).astype(np.float32)
+    idx, val, r_new = oracle.topk_ef(g, r, [0, n], [n])
+    np.testing.assert_array_equal(idx, np.arange(n))
+    assert_bits_equal(val, g + r)
+    assert np.all(bits(r_new) == 0)
+    g[17] = 100.0
+    g[400] = -100.0  # same magnitude later: lower index wins
+    idx, val, _ = oracle.topk_ef(g, np.zeros(n, np.float32), [0, n], [1])
+    assert idx.tolist() == [17] and val[0] == np.float32(100.0)
+
+
+def test_matches_library_topk_when_distinct():
+    rs = np.random.RandomState(4)
+    n, k = 100000, 1000
+    g = rs.permutation(n).astype(np.float32) * rs.choice([-1, 1], n).astype(np.float32)
+    idx, _, _ = oracle.topk_ef(g, np.zeros(n, np.float32), [0, n], [k])
+    want_np = np.sort(np.argpartition(-np.abs(g), k - 1)[:k])
+    np.testing.assert_array_equal(idx, want_np)
+    want_t = torch.topk(torch.from_numpy(g).abs(), k).indices.sort().values.numpy()
+    np.testing.assert_array_equal(idx, want_t)
+
+
+def test_all_zero_gradient_and_zero_diff_merge():
+    n, k = 5000, 50
+    z = np.zeros(n, dtype=np.float32)
+    idx, val, r_new = oracle.topk_ef(z, z, [0, n], [k])
+    np.testing.assert_array_equal(idx, np.arange(k))
+    assert np.all(bits(val) == 0) and np.all(bits(r_new) == 0)
+    w = np.random.RandomState(0).standard_normal(n).astype(np.float32)
+    w[:10] = -0.0  # w - (+0) keeps -0.0
+    assert_bits_equal(oracle.merge_sparse(w, [idx], [val], 0.1), w)
+
+
+def test_segments_are_independent():
+    wl = synth.workload("resnet50")
+    sizes = list(wl.sizes[:12])
+    off = synth.seg_offsets(sizes)
+    k = synth.seg_topk(sizes, 1, 100)
+    n = int(off[-1])
+    rs = np.random.RandomState(8)
+    g = rs.laplace(0, 1e-3, n).astype(np.float32)
+    r = rs.laplace(0, 1e-3, n).astype(np.float32)
+    idx, val, r_new = oracle.topk_ef(g, r, off, k)
+    pos = 0
+    for s in range(len(sizes)):
+        lo, hi = int(off[s]), int(off[s + 1])
+        i2, v2, r2 = oracle.topk_ef(g[lo:hi], r[lo:hi], [0, hi - lo], [k[s]])
+        np.testing.assert_array_equal(idx[pos:pos + k[s]], i2 + lo)
+        assert_bits_equal(val[pos:pos + k[s]], v2)
+        assert_bits_equal(r_new[lo:hi], r2)
+        pos += int(k[s])
+
+
+def test_sort_and_select_variants_agree():
+    for name, g, r in synth.adversarial_cases(3000, seed=1):
+        for k in (1, 30, 1500, 3000):
+            a = oracle.topk_ef(g, r, [0, 1000, 3000], [min(k, 1000), min(k, 2000)])
+            b = oracle.topk_ef(g, r, [0, 1000, 3000], [min(k, 1000), min(k, 2000)], select=True)
+            np.testing.assert_array_equal(a[0], b[0], err_msg=name)
+            assert_bits_equal(a[1], b[1])
+            assert_bits_equal(a[2], b[2])
+
+
+def test_denormals_and_signed_zero_preserved():
+    g = np.array([1e-41, -3e-42, 0.0, -0.0, 2e-45], dtype=np.float32)
+    r = np.array([1e-42, 1e-42, -0.0, -0.0, 0.0], dtype=np.float32)
+    idx, val, r_new = oracle.topk_ef(g, r, [0, 5], [2])
+    a = g + r
+    assert a[0] != 0 and a[1] != 0 and a[4] != 0           # not flushed
+    assert idx.tolist() == [0, 1]
+    assert_bits_equal(val, a[:2])
+    assert bits(r_new)[3] == 0x80000000                      # -0 + -0 = -0 kept
+    assert_bits_equal(r_new[2:], a[2:])
+
+
+def test_k_rule_matches_configuration():
+    # the flat configuration keeps 10,486 of 1,048,576 at 1% (ceil, not floor)
+    assert synth.seg_topk([1 << 20], 1, 100).tolist() == [10486]
+    assert synth.seg_topk([64, 1, 100, 101], 1, 100).tolist() == [1, 1, 1, 2]
+    for nm, n, nseg, K in (("resnet50", 25557032, 161, 255658), ("gpt2s", 124439808, 148, 124503),
+                           ("gpt2xl", 1557611200, 580, 15576112)):
+        wl = synth.workload(nm)
+        assert (wl.n, len(wl.sizes), int(wl.seg_k.astype(np.int64).sum())) == (n, nseg, K)
+    wl = synth.workload("llama7b")
+    assert (wl.n, len(wl.sizes)) == (6738415616, 291)
+
+
+# ---------------------------------------------------------------- sparse merge
+
+def test_golden_merge_worked_example():
+    lines = _read("merge_sparse_worked.txt")
+    L = {ln.split()[0]: ln for ln in lines if not ln.startswith("diff")}
+    idxs, vals = [], []
+    for ln in lines:
+        if ln.startswith("diff"):
+            tok = ln.split()
+            vi = tok.index("val")
+            idxs.append(np.array(tok[2:vi], dtype=np.int32))
+            vals.append(np.array(tok[vi + 1:], dtype=np.float32))
+    out = oracle.merge_sparse(_floats(L["w"]), idxs, vals, float(L["lr"].split()[1]))
+    assert_bits_equal(out, _floats(L["w_new"]))
+
+
+def _chain(n, W, seg_off, seg_k, seed=0, scale=1.0):
+    rs = np.random.RandomState(seed)
+    r = np.zeros(n, np.float32)
+    idxs, vals = [], []
+    for _ in range(W):
+        g = (rs.standard_normal(n) * scale).astype(np.float32)
+        i, v, r = oracle.topk_ef(g, r, seg_off, seg_k)
+        idxs.append(i)
+        vals.append(v)
+    return idxs, vals
+
+
+def test_window_merge_equals_sequential_and_prefix():
+    n, W = 20000, 7
+    idxs, vals = _chain(n, W, [0, 5000, n], [50, 150])
+    w0 = (np.random.RandomState(1).standard_normal(n) * 0.02).astype(np.float32)
+    lr = np.float32(0.1)
+    whole = oracle.merge_sparse(w0, idxs, vals, lr)
+    step = w0
+    for j in range(W):
+        step = oracle.merge_sparse(step, [idxs[j]], [vals[j]], lr)
+        assert_bits_equal(step, oracle.merge_sparse(w0, idxs[:j + 1], vals[:j + 1], lr))
+    assert_bits_equal(step, whole)
+    # independent statement of the same definition with numpy float32 ops
+    ref = w0.copy()
+    for j in range(W):
+        p = (lr * vals[j]).astype(np.float32)
+        ref[idxs[j]] = (ref[idxs[j]] - p).astype(np.float32)
+    assert_bits_equal(whole, ref)
+
+
+def test_merge_closed_form_counts():
+    n, W = 1000, 9
+    rs = np.random.RandomState(6)
+    w0 = rs.randint(-50, 50, n).astype(np.float32)
+    idxs = [np.sort(rs.choice(n, 100, replace=False)).astype(np.int32) for _ in range(W)]
+    vals = [np.ones(100, np.float32) for _ in range(W)]
+    cnt = np.zeros(n)
+    for i in idxs:
+        cnt[i] += 1
+    out = oracle.merge_sparse(w0, idxs, vals, 0.5)
+    np.testing.assert_array_equal(out, (w0 - 0.5 * cnt).astype(np.float32))
+
+
+def test_merge_respects_iteration_order():
+    # (w - p1) - p2 != (w - p2) - p1 in fp32 for these values
+    w = np.array([1.0], np.float32)
+    v1, v2 = np.array([-(2.0 ** -24 + 2.0 ** -30)], np.float32), np.array([1.0], np.float32)
+    i = [np.array([0], np.int32)] * 2
+    ab = oracle.merge_sparse(w, i, [v1, v2], 1.0)
+    ba = oracle.merge_sparse(w, i, [v2, v1], 1.0)
+    f = np.float32
+    assert ab[0] == f(f(f(1.0) - v1[0]) - v2[0]) and ba[0] == f(f(f(1.0) - v2[0]) - v1[0])
+    assert ab[0] != ba[0]
+    # never pre-summed: summing the two diffs first gives yet another value
+    w2 = np.array([2.0 ** 24], np.float32)
+    one = [np.array([-1.0], np.float32)] * 2
+    seq = oracle.merge_sparse(w2, i, one, 1.0)
+    assert seq[0] == f(2.0 ** 24) and f(w2[0] + f(2.0)) != seq[0]
+
+
+def test_merge_two_roundings_not_fma():
+    rs = np.random.RandomState(12)
+    n = 200000
+    w = rs.standard_normal(n).astype(np.float32)
+    val = rs.standard_normal(n).astype(np.float32)
+    lr = np.float32(0.1)
+    out = oracle.merge_sparse(w, [np.arange(n, dtype=np.int32)], [val], lr)
+    two = (w - (lr * val).astype(np.float32)).astype(np.float32)
+    fused = (w.astype(np.float64) - np.float64(lr) * val.astype(np.float64)).astype(np.float32)
+    assert_bits_equal(out, two)
+    assert np.any(bits(two) != bits(fused))  # the distinction is observable on this input
+
+
+# ---------------------------------------------------------------- snapshot
+
+def test_snapshot_is_bit_copy():
+    x = np.random.RandomState(0).randint(0, 1 << 16, 100003).astype(np.uint16)
+    y = oracle.snapshot(x)
+    np.testing.assert_array_equal(x, y)
+    assert y.ctypes.data != x.ctypes.data
+    assert oracle.snapshot(np.zeros(0, np.uint16)).shape == (0,)
+
+
+# ---------------------------------------------------------------- dense Adam
+
+def _bf16_bits(x):
+    return torch.tensor(x, dtype=torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def test_golden_adam_worked_example():
+    L = {}
+    for ln in _read("adam_worked.txt"):
+        L.setdefault(ln.split()[0], ln)
+    hp = dict(lr=float(L["lr"].split()[1]), beta1=float(L["beta1"].split()[1]),
+              beta2=float(L["beta2"].split()[1]), eps=float(L["eps"].split()[1]))
+    g = _floats(L["g"])
+    w0 = np.array([float(L["w0"].split()[1])], np.float32)
+    z = np.zeros(1, np.float32)
+    w1, m1, v1 = oracle.adam_replay(w0, z, z, [_bf16_bits([g[0]])], 0, **hp)
+    assert (w1[0], m1[0], v1[0]) == (0.875, 1.0, 1.0)
+    w2, m2, v2 = oracle.adam_replay(w0, z, z, [_bf16_bits([g[0]]), _bf16_bits([g[1]])], 0, **hp)
+    assert (w2[0], m2[0], v2[0]) == (0.875, 0.0, 1.0)
+    # continuing from the stored state equals replaying from scratch
+    w2b, m2b, v2b = oracle.adam_replay(w1, m1, v1, [_bf16_bits([g[1]])], 1, **hp)
+    assert (w2b[0], m2b[0], v2b[0]) == (0.875, 0.0, 1.0)
+    w3, m3, v3 = oracle.adam_replay(w2, m2, v2, [_bf16_bits([1.0])], 2, **hp)
+    assert (m3[0], v3[0]) == (0.5, 1.0)
+    assert w3[0] == np.float32(7.0 / 8.0 - math.sqrt(37.0) / 112.0)
+
+
+def test_adam_constant_gradient_closed_form():
+    # bias correction makes mhat = c and vhat = c^2 exactly, so every step moves
+    # w by lr*c/(|c|+eps)
+    n, T = 64, 25
+    c = np.linspace(-2, 2, n).astype(np.float32)
+    c = torch.tensor(c).to(torch.bfloat16).float().numpy()
+    gb = _bf16_bits(c)
+    lr, eps = 1e-2, 1e-8
+    w0 = np.ones(n, np.float32)
+    z = np.zeros(n, np.float32)
+    w, m, v = oracle.adam_replay(w0, z, z, [gb] * T, 0, lr, 0.9, 0.999, eps)
+    cd = c.astype(np.float64)
+    want = 1.0 - T * lr * cd / (np.abs(cd) + eps)
+    want[cd == 0] = 1.0
+    np.testing.assert_allclose(w, want, rtol=2e-6, atol=0)
+    np.testing.assert_allclose(m, cd * (1 - 0.9 ** T), rtol=1e-6)
+    np.testing.assert_allclose(v, cd * cd * (1 - np.float32(0.999).astype(np.float64) ** T), rtol=1e-5)
+    # first step from zero state: dw = -lr*g/(|g|+eps) whatever g is
+    w1, _, _ = oracle.adam_replay(w0, z, z, [gb], 0, lr, 0.9, 0.999, eps)
+    nz = cd != 0
+    np.testing.assert_allclose((w1 - w0)[nz], (-lr * np.sign(cd))[nz], rtol=1e-5)
+
+
+@pytest.mark.parametrize("step0", [0, 1000])
+def test_adam_matches_torch_optimizer(step0):
+    n, W = 4096, 5
+    rs = np.random.RandomState(21)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    grads = [torch.tensor(rs.standard_normal(n) * 1e-3, dtype=torch.float32).to(torch.bfloat16)
+             for _ in range(W)]
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8)
+    # fp32 storage rounds each state once per step: W * 2^-24 relative drift vs torch-in-double
+    for dtype, rtol in ((torch.float64, 5e-7), (torch.float32, 3e-6)):
+        p = torch.nn.Parameter(torch.tensor(w0, dtype=dtype))
+        opt = torch.optim.Adam([p], lr=hp["lr"], betas=(float(np.float32(0.9)), float(np.float32(0.999))),
+                               eps=hp["eps"], weight_decay=0, amsgrad=False)
+        # bring torch to `step0` with zero moments (what the oracle is given)
+        p.grad = torch.zeros_like(p)
+        opt.step()
+        st = opt.state[p]
+        st["step"].fill_(step0)
+        st["exp_avg"].zero_()
+        st["exp_avg_sq"].zero_()
+        with torch.no_grad():
+            p.copy_(torch.tensor(w0, dtype=dtype))
+        for g in grads:
+            p.grad = g.to(dtype)
+            opt.step()
+        z = np.zeros(n, np.float32)
+        w, m, v = oracle.adam_replay(w0, z, z, [g.view(torch.int16).numpy().view(np.uint16) for g in grads],
+                                     step0, **hp)
+        np.testing.assert_allclose(w, p.detach().numpy(), rtol=rtol, atol=1e-9)
+        # m sums signed terms of size ~1e-4: absolute drift W * 2^-24 * 3e-4 ~ 1e-10
+        np.testing.assert_allclose(m, st["exp_avg"].numpy(), rtol=rtol, atol=1e-10)
+        np.testing.assert_allclose(v, st["exp_avg_sq"].numpy(), rtol=rtol, atol=1e-15)
+
+
+def test_adam_window_equals_single_steps_and_zero_gradient():
+    n, W = 1000, 4
+    rs = np.random.RandomState(5)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    m0 = (rs.standard_normal(n) * 1e-4).astype(np.float32)
+    v0 = (rs.standard_normal(n) ** 2 * 1e-7).astype(np.float32)
+    gs = [_bf16_bits(rs.standard_normal(n) * 1e-3) for _ in range(W)]
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8)
+    a = oracle.adam_replay(w0, m0, v0, gs, 7, **hp)
+    w, m, v = w0, m0, v0
+    for t in range(W):
+        w, m, v = oracle.adam_replay(w, m, v, [gs[t]], 7 + t, **hp)
+    for x, y in zip(a, (w, m, v)):
+        assert_bits_equal(x, y)
+    # zero gradient with zero first moment: w, m unchanged, v decays by beta2
+    z = np.zeros(n, np.float32)
+    w2, m2, v2 = oracle.adam_replay(w0, z, v0, [np.zeros(n, np.uint16)], 3, **hp)
+    assert_bits_equal(w2, w0)
+    assert_bits_equal(m2, z)
+    np.testing.assert_allclose(v2, np.float64(np.float32(0.999)) * v0.astype(np.float64), rtol=1e-7)
+    # with m != 0 a zero gradient still moves w (Adam is not a "zero diff" no-op)
+    w3, _, _ = oracle.adam_replay(w0, m0, v0, [np.zeros(n, np.uint16)], 3, **hp)
+    assert np.any(w3 != w0)
+
+
+def test_bf16_widening_matches_torch():
+    allbits = np.arange(0, 1 << 16, dtype=np.uint16)
+    finite = ((allbits & 0x7F80) != 0x7F80) & (allbits != 0x8000)  # 0 + -0 = +0
+    hb = allbits[finite]
+    n = hb.shape[0]
+    z = np.zeros(n, np.float32)
+    # beta1 = 0: m becomes exactly the widened gradient
+    _, m, _ = oracle.adam_replay(z, z, z, [hb], 0, 0.0, 0.0, 0.0, 1.0)
+    want = torch.from_numpy(hb.view(np.int16)).view(torch.bfloat16).float().numpy()
+    assert_bits_equal(m, want)
