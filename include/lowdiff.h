@@ -1,0 +1,182 @@
+/*
+ * lowdiff.h - C ABI of the MI355X (gfx950) LowDiff hot-path library.
+ *
+ * The library turns each training iteration's gradient into a differential
+ * checkpoint and merges a window of such differentials onto a dense base
+ * checkpoint.  Four operations, all executed by hand-written HIP kernels:
+ *
+ *   ld_compress_topk     Comp of Algorithm 1 (Sec. IV-B): the compressed
+ *                        gradient that LowDiff reuses as the differential
+ *                        checkpoint C^D_t; sparsification at ratio rho
+ *                        (Sec. II-C, Sec. VII-A).
+ *   ld_merge_sparse      Recovery loop of Algorithm 1 / Eq. (6): load, decompress
+ *                        and merge the diffs of a window strictly in iteration
+ *                        order (Sec. IV-C, "Batched write semantics").
+ *   ld_snapshot_layer    Snapshot(G^n_t) of Algorithm 2 (Sec. VI-B): copy one
+ *                        layer's synchronized gradient out of the training
+ *                        buffer as soon as it exists.
+ *   ld_merge_dense_adam  "Merge in CPU" of Algorithm 2, M <- M + Adam(o_t, G_t)
+ *                        (Eq. (4)): incremental merge of dense diffs into the
+ *                        resident replica (kept in HBM here).
+ *
+ * General conventions
+ *   - Pointers marked "dev" are device (HBM) addresses of the current HIP
+ *     device; pointers marked "host" are ordinary host memory that the call
+ *     reads completely before it returns.
+ *   - Ownership: every buffer, workspaces included, is allocated, owned and
+ *     freed by the caller.  The library allocates nothing and keeps no state
+ *     between calls.
+ *   - Asynchrony: a call only enqueues kernels on `stream` (a hipStream_t
+ *     passed as void*; NULL is the default stream) and returns.  Results are
+ *     ready when the stream reaches that point.  Calls on one stream execute
+ *     in call order; that order is the iteration order of the diffs.
+ *   - Errors: argument errors are found on the host before anything is
+ *     enqueued; the call then returns a negative ld_status and touches no
+ *     buffer.  Data-dependent preconditions (indices in range and strictly
+ *     ascending inside a diff, no NaN among the values) are the caller's
+ *     contract and are not checked.
+ *   - Alignment: dev pointers to fp32 / int32 arrays must be 16-byte aligned
+ *     unless stated otherwise (LD_ERR_ALIGN).
+ *   - Inputs declared const are never written.
+ */
+#ifndef LOWDIFF_H_
+#define LOWDIFF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t ld_status;
+typedef void*   ld_stream; /* hipStream_t */
+
+#define LD_OK             0
+#define LD_ERR_NULL      -1 /* a required pointer is NULL                          */
+#define LD_ERR_RANGE     -2 /* a size, count or table entry is out of range        */
+#define LD_ERR_WORKSPACE -3 /* workspace missing, misaligned or too small          */
+#define LD_ERR_HIP       -4 /* a HIP runtime call or kernel launch failed          */
+#define LD_ERR_ALIGN     -5 /* a device pointer is not aligned as required         */
+
+/* Largest window one ld_merge_* call accepts. */
+#define LD_MAX_WINDOW 4096
+
+/* Human-readable name of a status code; never NULL; static storage. */
+const char* ld_status_string(ld_status s);
+
+/* ------------------------------------------------------------------------
+ * ld_compress_topk - per-segment top-k sparsification with error feedback.
+ *
+ * For every segment s = [seg_off[s], seg_off[s+1]) of the flat gradient:
+ *   a_i   = fl32(residual_i + grad_i)                (one IEEE add, RNE)
+ *   order : i before j  iff  |a_i| > |a_j|, or |a_i| == |a_j| and i < j
+ *           (|.| compared on the binary32 bit pattern with the sign cleared,
+ *            so +0 and -0 tie, and denormals are not flushed)
+ *   S     = the first seg_k[s] positions of that order
+ *   emit  : for i in S ascending: out_idx = i (global flat index),
+ *           out_val = a_i bit for bit; segment s's records start at
+ *           sum_{s'<s} seg_k[s']; the whole diff is strictly ascending in idx
+ *   residual_i <- +0.0f for i in S, a_i otherwise
+ * The result is unique (the order is total); it does not depend on launch
+ * shape or timing.
+ *
+ *   grad       dev  [n] fp32, read only, n = seg_off[n_seg] <= 2^31-1
+ *   residual   dev  [n] fp32, in/out
+ *   seg_off    host [n_seg+1] int64, seg_off[0] = 0, non-decreasing
+ *   seg_k      host [n_seg] int32, 0 <= seg_k[s] <= n_s
+ *   out_idx    dev  [K] int32, K = sum seg_k
+ *   out_val    dev  [K] fp32
+ *   workspace  dev, 256-byte aligned, at least ld_compress_topk_workspace()
+ *              bytes; contents on entry are irrelevant, contents on exit are
+ *              unspecified
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE (bad table, n > 2^31-1), LD_ERR_ALIGN,
+ * LD_ERR_WORKSPACE, LD_ERR_HIP.
+ */
+size_t    ld_compress_topk_workspace(int32_t n_seg, const int64_t* seg_off /* host */);
+ld_status ld_compress_topk(const float* grad, float* residual,
+                           const int64_t* seg_off, const int32_t* seg_k, int32_t n_seg,
+                           int32_t* out_idx, float* out_val,
+                           void* workspace, size_t workspace_bytes, ld_stream stream);
+
+/* ------------------------------------------------------------------------
+ * ld_snapshot_layer - bit-exact copy of one layer's bf16 gradient into a
+ * checkpoint-owned buffer, so training may overwrite its gradient buffer.
+ *
+ *   grad_bf16  dev [n_elems] 16-bit elements, read only (2-byte aligned is enough)
+ *   snap_bf16  dev [n_elems] destination; must not overlap the source
+ *   n_elems    >= 0 (0 enqueues nothing)
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE (n_elems < 0), LD_ERR_ALIGN (odd address),
+ * LD_ERR_HIP.
+ */
+ld_status ld_snapshot_layer(const void* grad_bf16, void* snap_bf16, int64_t n_elems,
+                            ld_stream stream);
+
+/* Same copy for many layers in one launch (small layers packed into one grid;
+ * the chunking/packing remark of Sec. VI-C "Snapshotting module").
+ *   src, dst  host arrays of n_layers dev pointers;  n_elems host [n_layers]
+ */
+ld_status ld_snapshot_layers(const void* const* src, void* const* dst, const int64_t* n_elems,
+                             int32_t n_layers, ld_stream stream);
+
+/* ------------------------------------------------------------------------
+ * ld_merge_sparse - replay a window of W sparse diffs onto w, in order:
+ *   for t = 0..W-1, for every record j of diff t:
+ *       p = fl32(lr * val[t][j]);  w[idx[t][j]] = fl32(w[idx[t][j]] - p)
+ * (two roundings, never a fused multiply-add).  One call with W diffs gives
+ * bit for bit the result of W calls with one diff each.
+ *
+ *   w          dev  [n] fp32 in/out, n <= 2^31-1
+ *   idx, val   host arrays of W dev pointers; idx[t] int32[K[t]] strictly
+ *              ascending and in [0, n); val[t] fp32[K[t]]
+ *   K          host [W] int64, 0 <= K[t] <= n
+ *   W          0 <= W <= LD_MAX_WINDOW (0 enqueues nothing)
+ *   workspace  dev, 256-byte aligned, ld_merge_sparse_workspace() bytes
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_WORKSPACE, LD_ERR_HIP.
+ */
+size_t    ld_merge_sparse_workspace(int64_t n, int32_t W, const int64_t* K /* host */);
+ld_status ld_merge_sparse(float* w, int64_t n,
+                          const int32_t* const* idx, const float* const* val,
+                          const int64_t* K, int32_t W, float lr,
+                          void* workspace, size_t workspace_bytes, ld_stream stream);
+
+/* Same operation with the execution strategy chosen by the caller (a tuning and
+ * test hook; the result is identical for every strategy):
+ *   LD_MERGE_AUTO     library decides from n and sum K
+ *   LD_MERGE_SWEEP    one streaming pass over w consuming all W diffs per tile
+ *   LD_MERGE_SCATTER  W scatter kernels, one per diff, in order
+ */
+#define LD_MERGE_AUTO    0
+#define LD_MERGE_SWEEP   1
+#define LD_MERGE_SCATTER 2
+ld_status ld_merge_sparse_strategy(float* w, int64_t n,
+                                   const int32_t* const* idx, const float* const* val,
+                                   const int64_t* K, int32_t W, float lr,
+                                   void* workspace, size_t workspace_bytes, ld_stream stream,
+                                   int32_t strategy);
+
+/* ------------------------------------------------------------------------
+ * ld_merge_dense_adam - replay W dense bf16 gradients through Adam onto the
+ * fp32 replica (w, m, v): for s = step0+1 .. step0+W with g = widen(grad_s),
+ *   m <- beta1*m + (1-beta1)*g
+ *   v <- beta2*v + (1-beta2)*g*g
+ *   w <- w - lr * (m / (1-beta1^s)) / (sqrt(v / (1-beta2^s)) + eps)
+ * in fp32 (bias-correction factors prepared on the host in double).  No weight
+ * decay, no AMSGrad.  A call with W gradients gives bit for bit the result of
+ * W calls with one gradient each.
+ *
+ *   w, m, v     dev  [n] fp32 in/out (n may exceed 2^32)
+ *   grads_bf16  host array of W dev pointers to bf16[n], 16-byte aligned
+ *   W           0 <= W <= 64
+ *   step0       >= 0, optimizer steps already contained in (w, m, v)
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_HIP.
+ */
+#define LD_MAX_ADAM_WINDOW 64
+ld_status ld_merge_dense_adam(float* w, float* m, float* v, int64_t n,
+                              const void* const* grads_bf16, int32_t W, int64_t step0,
+                              float lr, float beta1, float beta2, float eps, ld_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOWDIFF_H_ */

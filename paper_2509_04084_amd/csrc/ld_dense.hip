@@ -1,0 +1,249 @@
+// LowDiff+ dense path: layer snapshot and incremental Adam merge.
+//
+// ld_snapshot_layer(s): Snapshot(G^n_t) of Algorithm 2 (Sec. VI-B) - as soon as a
+//   layer's synchronized gradient exists it is copied, bit for bit, into a
+//   checkpoint-owned buffer so the backward pass may go on.  Here the copy stays
+//   in HBM (streaming 16-byte loads/stores); the multi-layer entry packs many
+//   small layers into one launch (Sec. VI-C, "Snapshotting module").
+// ld_merge_dense_adam: "Merge in CPU" of Algorithm 2, M <- M + Adam(o_t, G_t)
+//   (Eq. (4)), with the replica kept in HBM and the W steps of a window fused
+//   into one pass: (24 + 2W) bytes per parameter instead of 26 per step.
+#include <math.h>
+
+#include "ld_common.h"
+
+namespace {
+
+// ----------------------------------------------------------------- snapshot
+
+constexpr int kCopyThreads = 256;
+constexpr int kCopyUnroll = 4;                                    // 16-byte vectors per thread
+constexpr int64_t kCopyBlockBytes = kCopyThreads * kCopyUnroll * 16;  // 16 KB per block
+constexpr int kLayersPerLaunch = 128;
+
+struct CopyJob {
+    const unsigned char* src;
+    unsigned char* dst;
+    int64_t bytes;
+};
+
+struct CopyBatch {
+    CopyJob job[kLayersPerLaunch];
+    int32_t first_block[kLayersPerLaunch + 1];  // prefix of blocks per layer
+    int32_t n;
+};
+
+__device__ __forceinline__ void copy_block(const unsigned char* __restrict__ src,
+                                           unsigned char* __restrict__ dst, int64_t bytes,
+                                           int64_t blk) {
+    const int64_t b0 = blk * kCopyBlockBytes;
+    const int64_t b1 = (b0 + kCopyBlockBytes < bytes) ? b0 + kCopyBlockBytes : bytes;
+    const bool vec = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) == 0;
+    if (vec && b1 - b0 == kCopyBlockBytes) {
+        const ld_u32x4* s = reinterpret_cast<const ld_u32x4*>(src + b0);
+        ld_u32x4* d = reinterpret_cast<ld_u32x4*>(dst + b0);
+        ld_u32x4 x[kCopyUnroll];
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u) x[u] = ld_nt_load(s + u * kCopyThreads + threadIdx.x);
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u) ld_nt_store(x[u], d + u * kCopyThreads + threadIdx.x);
+    } else {
+        // ragged tail or unaligned layer: 2-byte elements
+        const uint16_t* s = reinterpret_cast<const uint16_t*>(src + b0);
+        uint16_t* d = reinterpret_cast<uint16_t*>(dst + b0);
+        const int32_t cnt = static_cast<int32_t>((b1 - b0) >> 1);
+        for (int32_t e = threadIdx.x; e < cnt; e += kCopyThreads) d[e] = s[e];
+    }
+}
+
+__global__ __launch_bounds__(kCopyThreads) void k_snapshot(const unsigned char* __restrict__ src,
+                                                           unsigned char* __restrict__ dst,
+                                                           int64_t bytes) {
+    copy_block(src, dst, bytes, blockIdx.x);
+}
+
+__global__ __launch_bounds__(kCopyThreads) void k_snapshot_batch(CopyBatch cb) {
+    // which layer does this block belong to: binary search in the block prefix
+    int lo = 0, hi = cb.n;
+    const int32_t blk = blockIdx.x;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cb.first_block[mid] <= blk) lo = mid; else hi = mid;
+    }
+    copy_block(cb.job[lo].src, cb.job[lo].dst, cb.job[lo].bytes, blk - cb.first_block[lo]);
+}
+
+// --------------------------------------------------------------------- Adam
+
+struct AdamArgs {
+    const uint16_t* grad[LD_MAX_ADAM_WINDOW];
+    float lr_over_bc1[LD_MAX_ADAM_WINDOW];  // lr / (1 - beta1^s)
+    float inv_bc2[LD_MAX_ADAM_WINDOW];      // 1 / (1 - beta2^s)
+    float beta1, one_m_beta1, beta2, one_m_beta2, eps;
+    int32_t W;
+};
+
+__device__ __forceinline__ float bf16_widen(uint32_t h) { return __uint_as_float(h << 16); }
+
+// One Adam step on one element; the only place the arithmetic is written, so a
+// fused window and a chain of single-step calls run the very same operations.
+__device__ __forceinline__ void adam_step(float& w, float& m, float& v, float g, float b1,
+                                          float omb1, float b2, float omb2, float eps,
+                                          float lr_bc1, float ibc2) {
+    m = __fmaf_rn(b1, m, __fmul_rn(omb1, g));
+    v = __fmaf_rn(b2, v, __fmul_rn(__fmul_rn(omb2, g), g));
+    const float denom = __fadd_rn(__builtin_amdgcn_sqrtf(__fmul_rn(v, ibc2)), eps);
+    const float upd = __fmul_rn(__fmul_rn(lr_bc1, m), __builtin_amdgcn_rcpf(denom));
+    w = __fsub_rn(w, upd);
+}
+
+constexpr int kAdamThreads = 256;
+constexpr int kAdamVec = 8;  // elements per thread per step: one 16-byte bf16 load
+
+__global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, float* __restrict__ m,
+                                                       float* __restrict__ v, int64_t n, AdamArgs a) {
+    const int64_t nvec = n / kAdamVec;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kAdamThreads;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kAdamThreads + threadIdx.x; i < nvec; i += stride) {
+        ld_f32x4 wv[2], mv[2], vv[2];
+        ld_f32x4* w4 = reinterpret_cast<ld_f32x4*>(w) + i * 2;
+        ld_f32x4* m4 = reinterpret_cast<ld_f32x4*>(m) + i * 2;
+        ld_f32x4* v4 = reinterpret_cast<ld_f32x4*>(v) + i * 2;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            wv[h] = ld_nt_load(w4 + h);
+            mv[h] = ld_nt_load(m4 + h);
+            vv[h] = ld_nt_load(v4 + h);
+        }
+        float ww[8] = {wv[0].x, wv[0].y, wv[0].z, wv[0].w, wv[1].x, wv[1].y, wv[1].z, wv[1].w};
+        float mm[8] = {mv[0].x, mv[0].y, mv[0].z, mv[0].w, mv[1].x, mv[1].y, mv[1].z, mv[1].w};
+        float v8[8] = {vv[0].x, vv[0].y, vv[0].z, vv[0].w, vv[1].x, vv[1].y, vv[1].z, vv[1].w};
+        for (int t = 0; t < a.W; ++t) {
+            const ld_u32x4 gq = ld_nt_load(reinterpret_cast<const ld_u32x4*>(a.grad[t]) + i);
+            const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
+            const float lr_bc1 = a.lr_over_bc1[t], ibc2 = a.inv_bc2[t];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t half = (e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu);
+                adam_step(ww[e], mm[e], v8[e], bf16_widen(half), a.beta1, a.one_m_beta1, a.beta2,
+                          a.one_m_beta2, a.eps, lr_bc1, ibc2);
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            ld_nt_store(ld_f32x4{ww[4 * h], ww[4 * h + 1], ww[4 * h + 2], ww[4 * h + 3]}, w4 + h);
+            ld_nt_store(ld_f32x4{mm[4 * h], mm[4 * h + 1], mm[4 * h + 2], mm[4 * h + 3]}, m4 + h);
+            ld_nt_store(ld_f32x4{v8[4 * h], v8[4 * h + 1], v8[4 * h + 2], v8[4 * h + 3]}, v4 + h);
+        }
+    }
+    // ragged tail (< 8 elements), one thread each
+    const int64_t tail0 = nvec * kAdamVec;
+    if (blockIdx.x == 0 && tail0 + threadIdx.x < n) {
+        const int64_t i = tail0 + threadIdx.x;
+        float ww = w[i], mm = m[i], v1 = v[i];
+        for (int t = 0; t < a.W; ++t)
+            adam_step(ww, mm, v1, bf16_widen(a.grad[t][i]), a.beta1, a.one_m_beta1, a.beta2,
+                      a.one_m_beta2, a.eps, a.lr_over_bc1[t], a.inv_bc2[t]);
+        w[i] = ww;
+        m[i] = mm;
+        v[i] = v1;
+    }
+}
+
+}  // namespace
+
+extern "C" ld_status ld_snapshot_layer(const void* grad_bf16, void* snap_bf16, int64_t n_elems,
+                                       ld_stream stream) {
+    if (n_elems < 0) return LD_ERR_RANGE;
+    if (n_elems == 0) return LD_OK;
+    if (!grad_bf16 || !snap_bf16) return LD_ERR_NULL;
+    if (!ld_aligned(grad_bf16, 2) || !ld_aligned(snap_bf16, 2)) return LD_ERR_ALIGN;
+    const int64_t bytes = n_elems * 2;
+    const int64_t blocks = (bytes + kCopyBlockBytes - 1) / kCopyBlockBytes;
+    if (blocks > INT32_MAX) return LD_ERR_RANGE;
+    k_snapshot<<<dim3(static_cast<uint32_t>(blocks)), dim3(kCopyThreads), 0,
+                 static_cast<hipStream_t>(stream)>>>(static_cast<const unsigned char*>(grad_bf16),
+                                                     static_cast<unsigned char*>(snap_bf16), bytes);
+    return ld_launch_status();
+}
+
+extern "C" ld_status ld_snapshot_layers(const void* const* src, void* const* dst,
+                                        const int64_t* n_elems, int32_t n_layers, ld_stream stream) {
+    if (n_layers < 0) return LD_ERR_RANGE;
+    if (n_layers == 0) return LD_OK;
+    if (!src || !dst || !n_elems) return LD_ERR_NULL;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (n_elems[l] < 0) return LD_ERR_RANGE;
+        if (n_elems[l] > 0 && (!src[l] || !dst[l])) return LD_ERR_NULL;
+        if (!ld_aligned(src[l], 2) || !ld_aligned(dst[l], 2)) return LD_ERR_ALIGN;
+        if ((n_elems[l] * 2 + kCopyBlockBytes - 1) / kCopyBlockBytes > (1 << 30)) return LD_ERR_RANGE;
+    }
+    int32_t l = 0;
+    while (l < n_layers) {
+        CopyBatch cb;
+        cb.n = 0;
+        int64_t blocks = 0;
+        cb.first_block[0] = 0;
+        while (l < n_layers && cb.n < kLayersPerLaunch) {
+            const int64_t bytes = n_elems[l] * 2;
+            const int64_t nb = (bytes + kCopyBlockBytes - 1) / kCopyBlockBytes;
+            if (nb == 0) { ++l; continue; }
+            if (blocks + nb > (1 << 30)) break;
+            cb.job[cb.n] = CopyJob{static_cast<const unsigned char*>(src[l]),
+                                   static_cast<unsigned char*>(dst[l]), bytes};
+            blocks += nb;
+            cb.first_block[++cb.n] = static_cast<int32_t>(blocks);
+            ++l;
+        }
+        if (cb.n == 0) continue;
+        for (int32_t j = cb.n; j < kLayersPerLaunch; ++j) {
+            cb.job[j] = CopyJob{nullptr, nullptr, 0};
+            cb.first_block[j + 1] = cb.first_block[cb.n];
+        }
+        k_snapshot_batch<<<dim3(static_cast<uint32_t>(blocks)), dim3(kCopyThreads), 0,
+                           static_cast<hipStream_t>(stream)>>>(cb);
+        if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
+    }
+    return LD_OK;
+}
+
+extern "C" ld_status ld_merge_dense_adam(float* w, float* m, float* v, int64_t n,
+                                         const void* const* grads_bf16, int32_t W, int64_t step0,
+                                         float lr, float beta1, float beta2, float eps,
+                                         ld_stream stream) {
+    if (n < 0 || W < 0 || W > LD_MAX_ADAM_WINDOW || step0 < 0) return LD_ERR_RANGE;
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f)) return LD_ERR_RANGE;
+    if (W == 0 || n == 0) return LD_OK;
+    if (!w || !m || !v || !grads_bf16) return LD_ERR_NULL;
+    if (!ld_aligned(w, 16) || !ld_aligned(m, 16) || !ld_aligned(v, 16)) return LD_ERR_ALIGN;
+    AdamArgs a;
+    for (int32_t t = 0; t < LD_MAX_ADAM_WINDOW; ++t) {
+        a.grad[t] = nullptr;
+        a.lr_over_bc1[t] = 0.0f;
+        a.inv_bc2[t] = 0.0f;
+    }
+    for (int32_t t = 0; t < W; ++t) {
+        if (!grads_bf16[t]) return LD_ERR_NULL;
+        if (!ld_aligned(grads_bf16[t], 16)) return LD_ERR_ALIGN;
+        a.grad[t] = static_cast<const uint16_t*>(grads_bf16[t]);
+        const double s = static_cast<double>(step0 + 1 + t);
+        const double bc1 = 1.0 - pow(static_cast<double>(beta1), s);
+        const double bc2 = 1.0 - pow(static_cast<double>(beta2), s);
+        a.lr_over_bc1[t] = static_cast<float>(static_cast<double>(lr) / bc1);
+        a.inv_bc2[t] = static_cast<float>(1.0 / bc2);
+    }
+    a.beta1 = beta1;
+    a.one_m_beta1 = 1.0f - beta1;
+    a.beta2 = beta2;
+    a.one_m_beta2 = 1.0f - beta2;
+    a.eps = eps;
+    a.W = W;
+    const int64_t nvec = n / kAdamVec;
+    int64_t blocks = (nvec + kAdamThreads - 1) / kAdamThreads;
+    const int64_t cap = 256 * 64;  // grid-stride beyond 64 blocks per CU
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    k_adam<<<dim3(static_cast<uint32_t>(blocks)), dim3(kAdamThreads), 0,
+             static_cast<hipStream_t>(stream)>>>(w, m, v, n, a);
+    return ld_launch_status();
+}

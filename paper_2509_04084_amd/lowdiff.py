@@ -1,0 +1,197 @@
+"""ctypes binding of the LowDiff C ABI (include/lowdiff.h): argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, hands their
+device addresses and the current HIP stream to the library, and returns.  All
+arithmetic happens in the HIP kernels; there is no fallback - if the library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from . import _build
+
+LD_OK = 0
+LD_MERGE_AUTO, LD_MERGE_SWEEP, LD_MERGE_SCATTER = 0, 1, 2
+LD_MAX_WINDOW = 4096
+LD_MAX_ADAM_WINDOW = 64
+
+_lib = None
+
+
+class LowDiffError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn}: {status_string(status)} ({status})")
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load() -> ctypes.CDLL:
+    """Loads liblowdiff.so (building it only if no built library is present)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_library(force=True)
+    lib = ctypes.CDLL(_build.LIB)
+    vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    lib.ld_status_string.argtypes = [i32]
+    lib.ld_status_string.restype = ctypes.c_char_p
+    lib.ld_compress_topk_workspace.argtypes = [i32, vp]
+    lib.ld_compress_topk_workspace.restype = sz
+    lib.ld_compress_topk.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.ld_compress_topk.restype = i32
+    lib.ld_snapshot_layer.argtypes = [vp, vp, i64, vp]
+    lib.ld_snapshot_layer.restype = i32
+    lib.ld_snapshot_layers.argtypes = [vp, vp, vp, i32, vp]
+    lib.ld_snapshot_layers.restype = i32
+    lib.ld_merge_sparse_workspace.argtypes = [i64, i32, vp]
+    lib.ld_merge_sparse_workspace.restype = sz
+    lib.ld_merge_sparse.argtypes = [vp, i64, vp, vp, vp, i32, f32, vp, sz, vp]
+    lib.ld_merge_sparse.restype = i32
+    lib.ld_merge_sparse_strategy.argtypes = [vp, i64, vp, vp, vp, i32, f32, vp, sz, vp, i32]
+    lib.ld_merge_sparse_strategy.restype = i32
+    lib.ld_merge_dense_adam.argtypes = [vp, vp, vp, i64, vp, i32, i64, f32, f32, f32, f32, vp]
+    lib.ld_merge_dense_adam.restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().ld_status_string(int(status)).decode()
+
+
+def _check(fn: str, status: int) -> None:
+    if status != LD_OK:
+        raise LowDiffError(fn, status)
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev(t: Optional[torch.Tensor], dtype, name: str) -> ctypes.c_void_p:
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous {dtype} tensor on the GPU")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _host(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hp(a: np.ndarray) -> ctypes.c_void_p:
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def ld_compress_topk_workspace(seg_off) -> int:
+    seg_off = _host(seg_off, np.int64)
+    return int(load().ld_compress_topk_workspace(seg_off.shape[0] - 1, _hp(seg_off)))
+
+
+def ld_compress_topk(grad: torch.Tensor, residual: torch.Tensor, seg_off, seg_k,
+                     out_idx: Optional[torch.Tensor] = None, out_val: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None, stream=None
+                     ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Per-segment top-k with error feedback; `residual` is updated in place.
+    Returns (out_idx int32[K], out_val float32[K])."""
+    lib = load()
+    seg_off = _host(seg_off, np.int64)
+    seg_k = _host(seg_k, np.int32)
+    n_seg = int(seg_k.shape[0])
+    if seg_off.shape[0] != n_seg + 1:
+        raise ValueError("seg_off must have n_seg + 1 entries")
+    K = int(seg_k.astype(np.int64).sum())
+    if out_idx is None:
+        out_idx = torch.empty(K, dtype=torch.int32, device=grad.device)
+    if out_val is None:
+        out_val = torch.empty(K, dtype=torch.float32, device=grad.device)
+    if out_idx.numel() < K or out_val.numel() < K:
+        raise ValueError("output buffers smaller than sum(seg_k)")
+    if workspace is None:
+        workspace = torch.empty(max(1, int(lib.ld_compress_topk_workspace(n_seg, _hp(seg_off)))),
+                                dtype=torch.uint8, device=grad.device)
+    st = lib.ld_compress_topk(_dev(grad, torch.float32, "grad"), _dev(residual, torch.float32, "residual"),
+                              _hp(seg_off), _hp(seg_k), n_seg,
+                              _dev(out_idx, torch.int32, "out_idx"), _dev(out_val, torch.float32, "out_val"),
+                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check("ld_compress_topk", st)
+    return out_idx, out_val
+
+
+def ld_snapshot_layer(grad_bf16: torch.Tensor, snap_bf16: torch.Tensor, stream=None) -> None:
+    if grad_bf16.numel() != snap_bf16.numel():
+        raise ValueError("snapshot source and destination differ in size")
+    st = load().ld_snapshot_layer(_dev(grad_bf16, torch.bfloat16, "grad_bf16"),
+                                  _dev(snap_bf16, torch.bfloat16, "snap_bf16"),
+                                  grad_bf16.numel(), _stream(stream))
+    _check("ld_snapshot_layer", st)
+
+
+def ld_snapshot_layers(srcs: Sequence[torch.Tensor], dsts: Sequence[torch.Tensor], stream=None) -> None:
+    n = len(srcs)
+    if len(dsts) != n:
+        raise ValueError("srcs and dsts differ in length")
+    sp = (ctypes.c_void_p * max(n, 1))(*[_dev(t, torch.bfloat16, "src").value or 0 for t in srcs])
+    dp = (ctypes.c_void_p * max(n, 1))(*[_dev(t, torch.bfloat16, "dst").value or 0 for t in dsts])
+    for a, b in zip(srcs, dsts):
+        if a.numel() != b.numel():
+            raise ValueError("snapshot source and destination differ in size")
+    ne = np.array([t.numel() for t in srcs], dtype=np.int64)
+    st = load().ld_snapshot_layers(sp, dp, _hp(ne), n, _stream(stream))
+    _check("ld_snapshot_layers", st)
+
+
+def ld_merge_sparse_workspace(n: int, K: Sequence[int]) -> int:
+    K = _host(K, np.int64)
+    return int(load().ld_merge_sparse_workspace(int(n), int(K.shape[0]), _hp(K)))
+
+
+def ld_merge_sparse(w: torch.Tensor, idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], lr: float,
+                    workspace: Optional[torch.Tensor] = None, stream=None,
+                    strategy: int = LD_MERGE_AUTO) -> None:
+    """Replays the diffs (idx[t], val[t]) onto `w` in list order, in place."""
+    lib = load()
+    W = len(idx)
+    if len(val) != W:
+        raise ValueError("idx and val differ in length")
+    K = np.array([t.numel() for t in idx], dtype=np.int64)
+    for a, b in zip(idx, val):
+        if a.numel() != b.numel():
+            raise ValueError("idx[t] and val[t] differ in size")
+    ip = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.int32, "idx").value or 0 for t in idx])
+    vp = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.float32, "val").value or 0 for t in val])
+    if workspace is None:
+        workspace = torch.empty(int(lib.ld_merge_sparse_workspace(w.numel(), W, _hp(K))),
+                                dtype=torch.uint8, device=w.device)
+    st = lib.ld_merge_sparse_strategy(_dev(w, torch.float32, "w"), w.numel(), ip, vp, _hp(K), W,
+                                      ctypes.c_float(lr), _dev(workspace, torch.uint8, "workspace"),
+                                      workspace.numel(), _stream(stream), int(strategy))
+    _check("ld_merge_sparse", st)
+
+
+def ld_merge_dense_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grads_bf16: Sequence[torch.Tensor],
+                        step0: int, lr: float, beta1: float, beta2: float, eps: float, stream=None) -> None:
+    """Replays the bf16 gradients as Adam steps step0+1.. onto (w, m, v), in place."""
+    W = len(grads_bf16)
+    for g in grads_bf16:
+        if g.numel() != w.numel():
+            raise ValueError("gradient and parameter sizes differ")
+    gp = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.bfloat16, "grad").value or 0 for t in grads_bf16])
+    st = load().ld_merge_dense_adam(_dev(w, torch.float32, "w"), _dev(m, torch.float32, "m"),
+                                    _dev(v, torch.float32, "v"), w.numel(), gp, W, int(step0),
+                                    ctypes.c_float(lr), ctypes.c_float(beta1), ctypes.c_float(beta2),
+                                    ctypes.c_float(eps), _stream(stream))
+    _check("ld_merge_dense_adam", st)

@@ -1,0 +1,105 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2509_04084_amd import lowdiff as ld
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a non-NULL, 256-byte aligned address that is never dereferenced on an error path
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "lowdiff.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ld_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ld.load()
+    names = declared_functions()
+    assert {"ld_compress_topk", "ld_snapshot_layer", "ld_merge_sparse", "ld_merge_dense_adam"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    assert ld.status_string(0) == "LD_OK"
+    for code in (-1, -2, -3, -4, -5):
+        assert ld.status_string(code).startswith("LD_ERR_")
+    assert "unknown" in ld.status_string(-99)
+
+
+def _p(a):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def test_compress_argument_errors():
+    lib = ld.load()
+    off = np.array([0, 100, 300], np.int64)
+    k = np.array([1, 2], np.int32)
+    ws_bytes = lib.ld_compress_topk_workspace(2, _p(off))
+    assert ws_bytes >= 256
+    V = ctypes.c_void_p
+
+    def call(grad=FAKE, res=FAKE, off=off, k=k, n_seg=2, oi=FAKE, ov=FAKE, ws=FAKE, wsb=ws_bytes):
+        return lib.ld_compress_topk(V(grad), V(res), _p(off) if off is not None else V(0),
+                                    _p(k) if k is not None else V(0), n_seg, V(oi), V(ov), V(ws), wsb, V(0))
+
+    assert call(grad=0) == -1 and call(res=0) == -1 and call(oi=0) == -1 and call(off=None) == -1
+    assert call(n_seg=-1) == -2
+    assert call(k=np.array([1, 201], np.int32)) == -2            # k_s > n_s
+    assert call(k=np.array([-1, 2], np.int32)) == -2
+    assert call(off=np.array([0, 300, 100], np.int64)) == -2      # decreasing
+    assert call(off=np.array([1, 100, 300], np.int64)) == -2      # does not start at 0
+    big = np.array([0, 2 ** 31], np.int64)
+    assert lib.ld_compress_topk(V(FAKE), V(FAKE), _p(big), _p(np.array([1], np.int32)), 1, V(FAKE), V(FAKE),
+                                V(FAKE), 1 << 40, V(0)) == -2     # n > 2^31 - 1
+    assert call(grad=FAKE + 4) == -5 and call(res=FAKE + 8) == -5
+    assert call(ws=0) == -3 and call(wsb=ws_bytes - 1) == -3 and call(ws=FAKE + 16) == -3
+    assert call(n_seg=0) == 0                                     # nothing to do
+    assert lib.ld_compress_topk_workspace(2, _p(np.array([0, 300, 100], np.int64))) == 0
+
+
+def test_merge_sparse_argument_errors():
+    lib = ld.load()
+    V = ctypes.c_void_p
+    K = np.array([10, 20], np.int64)
+    ptrs = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    wsb = lib.ld_merge_sparse_workspace(1000, 2, _p(K))
+
+    def call(w=FAKE, n=1000, idx=ptrs, val=ptrs, K=K, W=2, ws=FAKE, wsb=wsb, strat=1):
+        return lib.ld_merge_sparse_strategy(V(w), n, idx, val, _p(K), W, ctypes.c_float(0.1), V(ws), wsb,
+                                            V(0), strat)
+
+    assert call(w=0) == -1
+    assert call(n=-1) == -2 and call(n=2 ** 31) == -2 and call(W=-1) == -2 and call(W=ld.LD_MAX_WINDOW + 1) == -2
+    assert call(K=np.array([10, 1001], np.int64)) == -2 and call(K=np.array([-1, 5], np.int64)) == -2
+    assert call(idx=(ctypes.c_void_p * 2)(FAKE, 0)) == -1
+    assert call(w=FAKE + 4) == -5 and call(val=(ctypes.c_void_p * 2)(FAKE, FAKE + 2)) == -5
+    assert call(ws=0) == -3 and call(wsb=wsb - 1) == -3
+    assert call(strat=7) == -2
+    assert call(W=0) == 0 and call(n=0, K=np.array([0, 0], np.int64)) == 0
+
+
+def test_dense_argument_errors():
+    lib = ld.load()
+    V = ctypes.c_void_p
+    assert lib.ld_snapshot_layer(V(0), V(FAKE), 10, V(0)) == -1
+    assert lib.ld_snapshot_layer(V(FAKE), V(FAKE), -1, V(0)) == -2
+    assert lib.ld_snapshot_layer(V(FAKE + 1), V(FAKE), 10, V(0)) == -5
+    assert lib.ld_snapshot_layer(V(0), V(0), 0, V(0)) == 0
+    g = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    f = ctypes.c_float
+
+    def adam(w=FAKE, m=FAKE, v=FAKE, n=100, g=g, W=2, step0=0, b1=0.9, b2=0.999):
+        return lib.ld_merge_dense_adam(V(w), V(m), V(v), n, g, W, step0, f(1e-4), f(b1), f(b2), f(1e-8), V(0))
+
+    assert adam(w=0) == -1 and adam(g=(ctypes.c_void_p * 2)(FAKE, 0)) == -1
+    assert adam(n=-1) == -2 and adam(W=65) == -2 and adam(step0=-1) == -2 and adam(b1=1.0) == -2
+    assert adam(m=FAKE + 4) == -5 and adam(g=(ctypes.c_void_p * 2)(FAKE, FAKE + 2)) == -5
+    assert adam(W=0) == 0 and adam(n=0) == 0

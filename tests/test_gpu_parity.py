@@ -1,0 +1,289 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle,
+element by element on the same seeded inputs.
+
+Bars: bit-exact for indices, values, residuals, snapshots and sparse merges;
+|x - y| <= 1e-7 + 1e-6 |y| for the dense Adam replay (and a relative-only check
+on v, which never cancels).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_04084_amd import lowdiff as ld
+from paper_2509_04084_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+def to_gpu(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def check_compress(g, r, seg_off, seg_k, select=True, tag=""):
+    """Runs one compress call on both sides; returns (idx, val, r_new) of the oracle."""
+    print(f"[compress] {tag} n={len(g)} n_seg={len(seg_k)}", flush=True)
+    r_gpu = to_gpu(r)
+    idx, val = ld.ld_compress_topk(to_gpu(g), r_gpu, seg_off, seg_k)
+    torch.cuda.synchronize()
+    oi, ov, orr = oracle.topk_ef(g, r, seg_off, seg_k, select=select)
+    np.testing.assert_array_equal(idx.cpu().numpy(), oi, err_msg=f"idx {tag}")
+    np.testing.assert_array_equal(bits(val.cpu().numpy()), bits(ov), err_msg=f"val {tag}")
+    np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(orr), err_msg=f"residual {tag}")
+    return oi, ov, orr
+
+
+# ------------------------------------------------------------------ compress
+
+def test_compress_flat_1m_chained():
+    wl = synth.workload("flat1m")
+    off, k = wl.seg_off, wl.seg_k
+    r = np.zeros(wl.n, np.float32)
+    for t in range(3):
+        g = synth.gradient(wl, t).numpy()
+        _, _, r = check_compress(g, r, off, k, select=(t > 0), tag=f"flat1m t={t}")
+
+
+def test_compress_ragged_segments():
+    sizes = [1, 3, 64, 0, 4095, 4097, 65535, 65537, 2, 70001, 0, 200000, 131072, 5]
+    off = synth.seg_offsets(sizes)
+    rs = np.random.RandomState(1)
+    n = int(off[-1])
+    g = rs.standard_normal(n).astype(np.float32)
+    r = (rs.standard_normal(n) * 0.3).astype(np.float32)
+    check_compress(g, r, off, synth.seg_topk(sizes, 1, 100) * (np.array(sizes) > 0), tag="rho=1%")
+    check_compress(g, r, off, np.array(sizes, np.int32), tag="k=n")
+    check_compress(g, r, off, np.zeros(len(sizes), np.int32), tag="k=0")
+    check_compress(g, r, off, np.minimum(np.array(sizes), 1).astype(np.int32), tag="k=1")
+    check_compress(g, r, off, (np.array(sizes) // 2).astype(np.int32), tag="k=n/2")
+
+
+@pytest.mark.parametrize("n", [150001])
+def test_compress_adversarial(n):
+    off = np.array([0, 1000, 70000, n], np.int64)
+    for name, g, r in synth.adversarial_cases(n, seed=3):
+        for k in ([10, 690, 800], [1000, 1, 80001], [500, 69000, 40000]):
+            check_compress(g, r, off, np.array(k, np.int32), tag=f"{name} k={k}")
+
+
+def test_compress_resnet50_shape():
+    wl = synth.workload("resnet50")
+    g = synth.gradient(wl, 0).numpy()
+    r = (synth.gradient(wl, 1).numpy() * np.float32(0.5))
+    check_compress(g, r, wl.seg_off, wl.seg_k, tag="resnet50")
+
+
+def test_compress_is_deterministic_and_reads_only_grad():
+    wl = synth.workload("flat1m")
+    g = synth.gradient(wl, 5, device=DEV)
+    g0 = g.clone()
+    outs = []
+    for _ in range(2):
+        r = torch.zeros(wl.n, device=DEV)
+        i, v = ld.ld_compress_topk(g, r, wl.seg_off, wl.seg_k)
+        outs.append((i.clone(), v.clone(), r.clone()))
+    torch.cuda.synchronize()
+    assert torch.equal(g, g0)
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+# -------------------------------------------------------------- sparse merge
+
+def _diff_chain(wl, W, n=None):
+    n = wl.n if n is None else n
+    off = wl.seg_off
+    k = wl.seg_k
+    r = np.zeros(n, np.float32)
+    idxs, vals = [], []
+    for t in range(W):
+        g = synth.gradient(wl, t).numpy()
+        i, v, r = oracle.topk_ef(g, r, off, k, select=True)
+        idxs.append(i)
+        vals.append(v)
+    return idxs, vals
+
+
+@pytest.mark.parametrize("strategy", [ld.LD_MERGE_SWEEP, ld.LD_MERGE_SCATTER, ld.LD_MERGE_AUTO])
+def test_merge_flat_window(strategy):
+    wl = synth.workload("flat1m")
+    idxs, vals = _diff_chain(wl, wl.window)
+    w0 = synth.base_weights(wl.n).numpy()
+    ref = oracle.merge_sparse(w0, idxs, vals, wl.lr)
+    w = to_gpu(w0)
+    ld.ld_merge_sparse(w, [to_gpu(i) for i in idxs], [to_gpu(v) for v in vals], wl.lr, strategy=strategy)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref))
+    # the window in one call == one call per diff == any prefix
+    w2 = to_gpu(w0)
+    for j in range(wl.window):
+        ld.ld_merge_sparse(w2, [to_gpu(idxs[j])], [to_gpu(vals[j])], wl.lr, strategy=strategy)
+        if j == 3:
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(bits(w2.cpu().numpy()),
+                                          bits(oracle.merge_sparse(w0, idxs[:4], vals[:4], wl.lr)))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(w2.cpu().numpy()), bits(ref))
+
+
+@pytest.mark.parametrize("n,W,dens", [(1, 1, 1.0), (4095, 3, 0.5), (4097, 5, 0.02), (1000003, 9, 0.03),
+                                      (300000, 140, 0.004), (123457, 2, 1.0), (50000, 4, 0.0)])
+def test_merge_ragged_and_dense_windows(n, W, dens):
+    rs = np.random.RandomState(n % 1000 + W)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    idxs, vals = [], []
+    for t in range(W):
+        kk = int(round(n * dens)) if t != 1 else min(n, int(round(n * dens * 2)))
+        i = np.sort(rs.choice(n, kk, replace=False)).astype(np.int32)
+        idxs.append(i)
+        vals.append(rs.standard_normal(kk).astype(np.float32))
+    ref = oracle.merge_sparse(w0, idxs, vals, 0.1)
+    for strategy in (ld.LD_MERGE_SWEEP, ld.LD_MERGE_SCATTER):
+        w = to_gpu(w0)
+        ld.ld_merge_sparse(w, [to_gpu(i) for i in idxs], [to_gpu(v) for v in vals], 0.1, strategy=strategy)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref), err_msg=f"strategy {strategy}")
+
+
+def test_merge_order_and_zero_diff():
+    # order sensitivity: swapping two diffs changes the fp32 result; the GPU follows list order
+    n = 8192
+    w0 = np.ones(n, np.float32)
+    i = np.arange(n, dtype=np.int32)
+    v1 = np.full(n, -(2.0 ** -24 + 2.0 ** -30), np.float32)
+    v2 = np.ones(n, np.float32)
+    for order in ((v1, v2), (v2, v1)):
+        ref = oracle.merge_sparse(w0, [i, i], list(order), 1.0)
+        w = to_gpu(w0)
+        ld.ld_merge_sparse(w, [to_gpu(i), to_gpu(i)], [to_gpu(order[0]), to_gpu(order[1])], 1.0,
+                           strategy=ld.LD_MERGE_SWEEP)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref))
+    # a zero diff leaves w bit-identical, -0.0 weights included
+    w0 = np.random.RandomState(0).standard_normal(n).astype(np.float32)
+    w0[:100] = -0.0
+    w = to_gpu(w0)
+    ld.ld_merge_sparse(w, [to_gpu(i)], [to_gpu(np.zeros(n, np.float32))], 0.1, strategy=ld.LD_MERGE_SWEEP)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(w0))
+
+
+def test_compress_then_merge_end_to_end_resnet_window():
+    wl = synth.workload("resnet50")
+    W = 6
+    r_cpu = np.zeros(wl.n, np.float32)
+    r_gpu = torch.zeros(wl.n, device=DEV)
+    gi, gv, oi, ov = [], [], [], []
+    for t in range(W):
+        g = synth.gradient(wl, t).numpy()
+        a, b = ld.ld_compress_topk(to_gpu(g), r_gpu, wl.seg_off, wl.seg_k)
+        gi.append(a)
+        gv.append(b)
+        i, v, r_cpu = oracle.topk_ef(g, r_cpu, wl.seg_off, wl.seg_k, select=True)
+        oi.append(i)
+        ov.append(v)
+    w0 = synth.base_weights(wl.n).numpy()
+    w = to_gpu(w0)
+    ld.ld_merge_sparse(w, gi, gv, wl.lr)
+    torch.cuda.synchronize()
+    for t in range(W):
+        np.testing.assert_array_equal(gi[t].cpu().numpy(), oi[t])
+        np.testing.assert_array_equal(bits(gv[t].cpu().numpy()), bits(ov[t]))
+    np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(r_cpu))
+    np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(oracle.merge_sparse(w0, oi, ov, wl.lr)))
+
+
+# ------------------------------------------------------------------ snapshot
+
+@pytest.mark.parametrize("n", [0, 1, 7, 8191, 8192, 1 << 20, (1 << 20) + 3, 11008 * 4096])
+def test_snapshot_bit_exact(n):
+    src = torch.randint(-32768, 32767, (n + 9,), dtype=torch.int16, device=DEV).view(torch.bfloat16)
+    for shift in (0, 1):  # 16-byte aligned and 2-byte aligned views
+        s = src[shift:shift + n]
+        d = torch.zeros(n + 2, dtype=torch.bfloat16, device=DEV)
+        ld.ld_snapshot_layer(s, d[1:1 + n] if shift else d[:n])
+        torch.cuda.synchronize()
+        got = (d[1:1 + n] if shift else d[:n]).view(torch.int16).cpu().numpy().view(np.uint16)
+        ref = oracle.snapshot(s.view(torch.int16).cpu().numpy().view(np.uint16))
+        np.testing.assert_array_equal(got, ref)
+        rest = d[:1] if shift else d[n:]
+        assert torch.all(rest.view(torch.int16) == 0)  # nothing written outside
+
+
+def test_snapshot_many_layers_one_launch():
+    wl = synth.workload("llama7b")
+    sizes = [s // 64 for s in wl.sizes[:40]] + [0, 1, 17]
+    srcs = [torch.randint(-32768, 32767, (s,), dtype=torch.int16, device=DEV).view(torch.bfloat16) for s in sizes]
+    dsts = [torch.zeros_like(s) for s in srcs]
+    ld.ld_snapshot_layers(srcs, dsts)
+    torch.cuda.synchronize()
+    for a, b in zip(srcs, dsts):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+# ---------------------------------------------------------------------- Adam
+
+def _bf16_bits_t(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def check_adam_close(got, ref, tag):
+    for name, a, b in zip("wmv", got, ref):
+        a = a.cpu().numpy().astype(np.float64)
+        b = b.astype(np.float64)
+        err = np.abs(a - b)
+        assert np.all(err <= 1e-7 + 1e-6 * np.abs(b)), f"{tag} {name}: max err {err.max()}"
+    # v is a sum of non-negative terms: hold it to the relative bound alone
+    a, b = got[2].cpu().numpy().astype(np.float64), ref[2].astype(np.float64)
+    assert np.all(np.abs(a - b) <= 1e-6 * np.abs(b)), f"{tag} v relative"
+
+
+@pytest.mark.parametrize("n", [1, 7, 8, 1000003])
+@pytest.mark.parametrize("W,step0", [(1, 0), (4, 0), (3, 1000)])
+def test_adam_replay_parity(n, W, step0):
+    rs = np.random.RandomState(n % 97 + W)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    m0 = np.zeros(n, np.float32) if step0 == 0 else (rs.standard_normal(n) * 1e-4).astype(np.float32)
+    v0 = np.zeros(n, np.float32) if step0 == 0 else (rs.standard_normal(n) ** 2 * 1e-7).astype(np.float32)
+    grads = [to_gpu((rs.standard_normal(n) * 1e-3).astype(np.float32)).to(torch.bfloat16) for _ in range(W)]
+    hp = dict(lr=1e-4, **synth.ADAM)
+    ref = oracle.adam_replay(w0, m0, v0, [_bf16_bits_t(g) for g in grads], step0, **hp)
+    w, m, v = to_gpu(w0), to_gpu(m0), to_gpu(v0)
+    ld.ld_merge_dense_adam(w, m, v, grads, step0, **hp)
+    torch.cuda.synchronize()
+    check_adam_close((w, m, v), ref, f"n={n} W={W} step0={step0}")
+    # fused window == chain of single-step calls, bit for bit
+    w2, m2, v2 = to_gpu(w0), to_gpu(m0), to_gpu(v0)
+    for t in range(W):
+        ld.ld_merge_dense_adam(w2, m2, v2, [grads[t]], step0 + t, **hp)
+    torch.cuda.synchronize()
+    for a, b in ((w, w2), (m, m2), (v, v2)):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def test_adam_zero_gradient_and_closed_form():
+    n = 4096
+    hp = dict(lr=1e-2, **synth.ADAM)
+    w0 = np.random.RandomState(2).standard_normal(n).astype(np.float32)
+    v0 = (np.random.RandomState(3).standard_normal(n) ** 2 * 1e-6).astype(np.float32)
+    w, m, v = to_gpu(w0), torch.zeros(n, device=DEV), to_gpu(v0)
+    ld.ld_merge_dense_adam(w, m, v, [torch.zeros(n, dtype=torch.bfloat16, device=DEV)], 5, **hp)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(w0))
+    assert torch.all(m == 0)
+    np.testing.assert_allclose(v.cpu().numpy(), np.float64(np.float32(0.999)) * v0, rtol=1e-6)
+    # constant gradient from zero state: every step moves w by lr*c/(|c|+eps)
+    c = torch.linspace(-2, 2, n, device=DEV).to(torch.bfloat16)
+    T = 20
+    w, m, v = torch.ones(n, device=DEV), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    ld.ld_merge_dense_adam(w, m, v, [c] * T, 0, **hp)
+    torch.cuda.synchronize()
+    cd = c.float().cpu().numpy().astype(np.float64)
+    want = 1.0 - T * hp["lr"] * cd / (np.abs(cd) + hp["eps"])
+    want[cd == 0] = 1.0
+    np.testing.assert_allclose(w.cpu().numpy(), want, rtol=3e-6)
