@@ -1,0 +1,297 @@
+#!/usr/bin/env python3
+"""Benchmark of the LowDiff hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic gradients:
+
+  sparse leg (GPT-2-XL-shaped, 1.56 B fp32 parameters, 580 segments, rho = 1 %):
+      W = 20 chained ld_compress_topk calls (error-feedback residual carried from
+      call to call) followed by one ld_merge_sparse of the 20-diff window;
+  dense leg (Llama-7B-shaped, 6.74 B parameters, fp32 w/m/v, bf16 gradients):
+      W = 4 iterations of layer-wise ld_snapshot_layer (291 layers each) followed
+      by one fused ld_merge_dense_adam of the 4 snapshots.
+
+All inputs are resident in HBM before the timed region.  State (residual, w, m, v)
+is carried from step to step, as in training: nothing is restored inside the
+timed region.  `value` is gradient bytes turned into (and merged from)
+differential checkpoints per second over the whole step.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2509_04084_amd import lowdiff as ld  # noqa: E402
+from paper_2509_04084_amd import synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Timer:
+    """HIP-event pairs on the current stream (the stream the library launches on)."""
+
+    def __init__(self):
+        self.pairs = {}
+
+    def start(self, name):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        return name, e0
+
+    def stop(self, tok):
+        name, e0 = tok
+        e1 = torch.cuda.Event(enable_timing=True)
+        e1.record()
+        self.pairs.setdefault(name, []).append((e0, e1))
+
+    def ms(self):
+        return {k: [a.elapsed_time(b) for a, b in v] for k, v in self.pairs.items()}
+
+
+class SparseLeg:
+    def __init__(self, wl, dev, pool):
+        self.wl, self.dev = wl, dev
+        self.off, self.k = wl.seg_off, wl.seg_k
+        self.n, self.W = wl.n, wl.window
+        self.K = int(self.k.astype(np.int64).sum())
+        log(f"[sparse] {wl.name}: n={self.n:,} segs={len(wl.sizes)} K={self.K:,} W={self.W} pool={pool}")
+        self.grads = [synth.gradient(wl, t, device=dev) for t in range(pool)]
+        self.r = torch.zeros(self.n, dtype=torch.float32, device=dev)
+        self.w = synth.base_weights(self.n, device=dev, std=wl.w_std)
+        self.idx = [torch.empty(self.K, dtype=torch.int32, device=dev) for _ in range(self.W)]
+        self.val = [torch.empty(self.K, dtype=torch.float32, device=dev) for _ in range(self.W)]
+        self.ws_c = torch.empty(ld.ld_compress_topk_workspace(self.off), dtype=torch.uint8, device=dev)
+        self.ws_m = torch.empty(ld.ld_merge_sparse_workspace(self.n, [self.K] * self.W), dtype=torch.uint8,
+                                device=dev)
+        self.it = 0
+
+    def step(self, tm):
+        for t in range(self.W):
+            g = self.grads[self.it % len(self.grads)]
+            tok = tm.start("compress")
+            ld.ld_compress_topk(g, self.r, self.off, self.k, self.idx[t], self.val[t], self.ws_c)
+            tm.stop(tok)
+            self.it += 1
+        tok = tm.start("merge_sparse")
+        ld.ld_merge_sparse(self.w, self.idx, self.val, self.wl.lr, self.ws_m)
+        tm.stop(tok)
+
+    # algorithmic bytes per call
+    def bytes_compress(self):
+        return 12 * self.n + 8 * self.K
+
+    def bytes_merge(self):
+        return 8 * self.n + 8 * self.K * self.W
+
+    def grad_bytes(self):
+        return 4 * self.n * self.W
+
+
+class DenseLeg:
+    def __init__(self, wl, dev, n_src=2):
+        self.wl, self.dev = wl, dev
+        self.n, self.W = wl.n, wl.window
+        self.off = wl.seg_off
+        log(f"[dense] {wl.name}: n={self.n:,} layers={len(wl.sizes)} W={self.W}")
+        self.src = []
+        for t in range(n_src):
+            g = torch.empty(self.n, dtype=torch.bfloat16, device=dev)
+            for s in range(len(wl.sizes)):  # layer by layer: bounds the fp32 temporary
+                lo, hi = int(self.off[s]), int(self.off[s + 1])
+                g[lo:hi] = synth.gradient_layer_bf16(wl, t, s, dev)
+            self.src.append(g)
+        self.snap = [torch.empty(self.n, dtype=torch.bfloat16, device=dev) for _ in range(self.W)]
+        self.w = synth.base_weights(self.n, device=dev, std=wl.w_std)
+        self.m = torch.zeros(self.n, dtype=torch.float32, device=dev)
+        self.v = torch.zeros(self.n, dtype=torch.float32, device=dev)
+        self.layers = [(int(self.off[s]), int(self.off[s + 1])) for s in range(len(wl.sizes))]
+        # backward order: last layer's gradient exists first
+        self.src_views = [[g[lo:hi] for lo, hi in reversed(self.layers)] for g in self.src]
+        self.snap_views = [[g[lo:hi] for lo, hi in reversed(self.layers)] for g in self.snap]
+        self.step0 = 0
+        self.it = 0
+
+    def step(self, tm):
+        for t in range(self.W):
+            sv = self.src_views[self.it % len(self.src)]
+            dv = self.snap_views[t]
+            tok = tm.start("snapshot_iter")
+            for a, b in zip(sv, dv):
+                ld.ld_snapshot_layer(a, b)
+            tm.stop(tok)
+            self.it += 1
+        tok = tm.start("adam")
+        ld.ld_merge_dense_adam(self.w, self.m, self.v, self.snap, self.step0, self.wl.lr, **synth.ADAM)
+        tm.stop(tok)
+        self.step0 += self.W
+
+    def bytes_snapshot_iter(self):
+        return 4 * self.n
+
+    def bytes_adam(self):
+        return (24 + 2 * self.W) * self.n
+
+    def grad_bytes(self):
+        return 2 * self.n * self.W
+
+
+def cpu_baseline(budget_hint_s=20.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import oracle
+    xl, ll = synth.workload("gpt2xl"), synth.workload("llama7b")
+    segs = [4, 10, 12]  # one block's qkv, fc and proj weights: 7.68 M + 10.24 M + 10.24 M elements
+    sizes = [xl.sizes[s] for s in segs]
+    off, k = synth.seg_offsets(sizes), synth.seg_topk(sizes, *xl.rho)
+    n = int(off[-1])
+    Wc = 4
+    grads = []
+    for t in range(Wc):
+        g = np.empty(n, np.float32)
+        for j, s in enumerate(segs):
+            g[off[j]:off[j + 1]] = synth.gradient_segment(xl, t, s, "cpu").numpy()
+        grads.append(g)
+    w0 = synth.base_weights(n).numpy()
+    t0 = time.perf_counter()
+    r = np.zeros(n, np.float32)
+    idxs, vals = [], []
+    for g in grads:
+        i, v, r = oracle.topk_ef(g, r, off, k, select=True)
+        idxs.append(i)
+        vals.append(v)
+    oracle.merge_sparse(w0, idxs, vals, xl.lr)
+    t_sparse = time.perf_counter() - t0
+    sparse_bytes = 4 * n * Wc
+    # dense: one attention projection layer (16.8 M elements), W = 4
+    nd, Wd = ll.sizes[1], ll.window
+    gs = [synth.gradient_layer_bf16(ll, t, 1, "cpu").view(torch.int16).numpy().view(np.uint16) for t in range(Wd)]
+    wd = synth.base_weights(nd).numpy()
+    z = np.zeros(nd, np.float32)
+    t0 = time.perf_counter()
+    snaps = [oracle.snapshot(g) for g in gs]
+    oracle.adam_replay(wd, z, z, snaps, 0, ll.lr, **synth.ADAM)
+    t_dense = time.perf_counter() - t0
+    dense_bytes = 2 * nd * Wd
+    # weight the two legs as the full step does (gradient bytes of each leg)
+    full_sparse = 4 * xl.n * xl.window
+    full_dense = 2 * ll.n * ll.window
+    est_full_s = t_sparse * full_sparse / sparse_bytes + t_dense * full_dense / dense_bytes
+    value = (full_sparse + full_dense) / est_full_s / 1e9
+    return {
+        "value": value, "unit": "GB/s (gradient bytes)", "cores": 1, "kind": "oracle",
+        "sample": (f"gpt2xl segments {segs} ({n:,} elements), {Wc} chained top-k (nth_element variant) + "
+                   f"window merge: {t_sparse:.2f} s; llama7b layer 1 ({nd:,} elements), snapshot + Adam "
+                   f"replay W={Wd}: {t_dense:.2f} s; extrapolated to the full step by gradient bytes"),
+        "sparse_GBps": sparse_bytes / t_sparse / 1e9, "dense_GBps": dense_bytes / t_dense / 1e9,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--pool", type=int, default=10, help="distinct gradients cycled by the sparse leg")
+    ap.add_argument("--sparse", default="gpt2xl")
+    ap.add_argument("--dense", default="llama7b")
+    ap.add_argument("--legs", default="sparse,dense")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ld.load()
+    legs = args.legs.split(",")
+    t_setup = time.perf_counter()
+    sparse = SparseLeg(synth.workload(args.sparse), dev, args.pool) if "sparse" in legs else None
+    dense = DenseLeg(synth.workload(args.dense), dev) if "dense" in legs else None
+    torch.cuda.synchronize()
+    log(f"[setup] {time.perf_counter() - t_setup:.1f} s, {torch.cuda.memory_allocated() / 1e9:.1f} GB resident")
+
+    def one_step(tm):
+        if sparse:
+            sparse.step(tm)
+        if dense:
+            dense.step(tm)
+
+    for i in range(args.warmup):
+        one_step(Timer())
+        torch.cuda.synchronize()
+        log(f"[warmup] {i + 1}/{args.warmup}")
+    tm = Timer()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(tm)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    per = {k: float(np.mean(v)) for k, v in tm.ms().items()}
+    log(f"[timed] {args.steps} steps, {ms_per_step:.2f} ms/step; mean ms per call: {per}")
+
+    grad_bytes = (sparse.grad_bytes() if sparse else 0) + (dense.grad_bytes() if dense else 0)
+    value = grad_bytes / (ms_per_step * 1e-3) / 1e9
+
+    def roof(name, nbytes):
+        ach = nbytes / (per[name] * 1e-3) / 1e9
+        return {"ms": per[name], "algorithmic_bytes": nbytes, "achieved_GBps": ach, "frac": ach / HBM_PEAK_GBS}
+
+    calls = {}
+    if sparse:
+        calls["ld_compress_topk"] = roof("compress", sparse.bytes_compress())
+        calls["ld_merge_sparse"] = roof("merge_sparse", sparse.bytes_merge())
+        calls["ld_compress_topk"]["grad_GBps"] = 4 * sparse.n / (per["compress"] * 1e-3) / 1e9
+        calls["ld_merge_sparse"]["grad_GBps"] = 4 * sparse.n * sparse.W / (per["merge_sparse"] * 1e-3) / 1e9
+    if dense:
+        calls["ld_snapshot_layer(x291)"] = roof("snapshot_iter", dense.bytes_snapshot_iter())
+        calls["ld_merge_dense_adam"] = roof("adam", dense.bytes_adam())
+    # the call that takes the largest share of the step
+    share = {}
+    if sparse:
+        share["ld_compress_topk"] = per["compress"] * sparse.W
+        share["ld_merge_sparse"] = per["merge_sparse"]
+    if dense:
+        share["ld_snapshot_layer(x291)"] = per["snapshot_iter"] * dense.W
+        share["ld_merge_dense_adam"] = per["adam"]
+    dom = max(share, key=share.get)
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": calls[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": calls[dom]["frac"], "traffic": None,
+                "note": "per call of the entry point (all its kernels), HIP events on the launch stream"}
+    out = {
+        "metric": "diff-build GB/s + merge GB/s (grad bytes), % of MI355X HBM roofline",
+        "value": value, "unit": "GB/s (gradient bytes)", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "+".join(x for x in (args.sparse if sparse else None,
+                                                    args.dense if dense else None) if x),
+                   "sparse": (f"{args.sparse}: n={sparse.n} segs={len(sparse.wl.sizes)} rho=1% W={sparse.W} "
+                              f"chained compress + window merge") if sparse else None,
+                   "dense": (f"{args.dense}: n={dense.n} layers={len(dense.wl.sizes)} W={dense.W} "
+                             f"layer snapshots + fused Adam replay") if dense else None},
+        "roofline": roofline, "calls": calls,
+    }
+    if not args.no_cpu_baseline:
+        log("[cpu_baseline] timing the oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -152,31 +152,35 @@ def segment_scales(wl: Workload) -> np.ndarray:
     return np.full(len(wl.sizes), wl.scale, dtype=np.float64)
 
 
-def gradient(wl: Workload, t: int, device="cpu", out: Optional[torch.Tensor] = None,
-             segments: Optional[Sequence[int]] = None) -> torch.Tensor:
-    """Iteration t's flat fp32 gradient (seed = t).  With `segments`, only those
-    segments are drawn (others left as they are in `out`); a segment's values do
-    not depend on which other segments are drawn."""
-    n = wl.n
-    if out is None:
-        out = torch.zeros(n, dtype=torch.float32, device=device)
-    off = wl.seg_off
-    scales = segment_scales(wl)
+def gradient_segment(wl: Workload, t: int, s: int, device="cpu") -> torch.Tensor:
+    """Segment s of iteration t's gradient as fp32; independent of every other segment."""
+    count = int(wl.sizes[s])
+    scale = float(segment_scales(wl)[s])
     dist = "normal" if wl.dist == "bf16_normal" else wl.dist
-    todo = range(len(wl.sizes)) if segments is None else segments
-    for s in todo:
-        gen = _gen(device, (int(t) * 1_000_003 + s * 7919 + 17) & 0x7FFFFFFFFFFF)
-        lo, hi = int(off[s]), int(off[s + 1])
-        for c0 in range(lo, hi, _CHUNK):
-            c1 = min(hi, c0 + _CHUNK)
-            out[c0:c1] = _draw(dist, c1 - c0, gen, device, float(scales[s]))
+    gen = _gen(device, (int(t) * 1_000_003 + s * 7919 + 17) & 0x7FFFFFFFFFFF)
+    out = torch.empty(count, dtype=torch.float32, device=device)
+    for c0 in range(0, count, _CHUNK):
+        c1 = min(count, c0 + _CHUNK)
+        out[c0:c1] = _draw(dist, c1 - c0, gen, device, scale)
     return out
 
 
-def gradient_bf16(wl: Workload, t: int, device="cpu",
-                  segments: Optional[Sequence[int]] = None) -> torch.Tensor:
-    """Dense-path gradient rounded (nearest even) to bf16."""
-    return gradient(wl, t, device, segments=segments).to(torch.bfloat16)
+def gradient(wl: Workload, t: int, device="cpu", out: Optional[torch.Tensor] = None,
+             segments: Optional[Sequence[int]] = None) -> torch.Tensor:
+    """Iteration t's flat fp32 gradient (seed = t).  With `segments`, only those
+    segments are drawn (others left as they are in `out`)."""
+    if out is None:
+        out = torch.zeros(wl.n, dtype=torch.float32, device=device)
+    off = wl.seg_off
+    todo = range(len(wl.sizes)) if segments is None else segments
+    for s in todo:
+        out[int(off[s]):int(off[s + 1])] = gradient_segment(wl, t, s, device)
+    return out
+
+
+def gradient_layer_bf16(wl: Workload, t: int, s: int, device="cpu") -> torch.Tensor:
+    """Dense-path gradient of one layer, rounded (nearest even) to bf16."""
+    return gradient_segment(wl, t, s, device).to(torch.bfloat16)
 
 
 def base_weights(n: int, device="cpu", std: float = 0.02) -> torch.Tensor:
