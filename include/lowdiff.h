@@ -99,6 +99,22 @@ ld_status ld_compress_topk(const float* grad, float* residual,
                            int32_t* out_idx, float* out_val,
                            void* workspace, size_t workspace_bytes, ld_stream stream);
 
+/* Same operation with the selection strategy chosen by the caller (a tuning and
+ * test hook; the result is identical for every strategy):
+ *   LD_COMPRESS_AUTO  one streaming pass; a per-segment candidate threshold is
+ *                     estimated from a sample, the exact top-k is then resolved
+ *                     among the candidates (segments whose estimate turns out
+ *                     too high are redone by the FULL method)
+ *   LD_COMPRESS_FULL  no estimate: multi-pass radix select over whole segments
+ */
+#define LD_COMPRESS_AUTO 0
+#define LD_COMPRESS_FULL 1
+ld_status ld_compress_topk_strategy(const float* grad, float* residual,
+                                    const int64_t* seg_off, const int32_t* seg_k, int32_t n_seg,
+                                    int32_t* out_idx, float* out_val,
+                                    void* workspace, size_t workspace_bytes, ld_stream stream,
+                                    int32_t strategy);
+
 /* ------------------------------------------------------------------------
  * ld_snapshot_layer - bit-exact copy of one layer's bf16 gradient into a
  * checkpoint-owned buffer, so training may overwrite its gradient buffer.

@@ -18,6 +18,7 @@ from . import _build
 
 LD_OK = 0
 LD_MERGE_AUTO, LD_MERGE_SWEEP, LD_MERGE_SCATTER = 0, 1, 2
+LD_COMPRESS_AUTO, LD_COMPRESS_FULL = 0, 1
 LD_MAX_WINDOW = 4096
 LD_MAX_ADAM_WINDOW = 64
 
@@ -49,6 +50,8 @@ def load() -> ctypes.CDLL:
     lib.ld_compress_topk_workspace.restype = sz
     lib.ld_compress_topk.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.ld_compress_topk.restype = i32
+    lib.ld_compress_topk_strategy.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, sz, vp, i32]
+    lib.ld_compress_topk_strategy.restype = i32
     lib.ld_snapshot_layer.argtypes = [vp, vp, i64, vp]
     lib.ld_snapshot_layer.restype = i32
     lib.ld_snapshot_layers.argtypes = [vp, vp, vp, i32, vp]
@@ -103,8 +106,8 @@ def ld_compress_topk_workspace(seg_off) -> int:
 
 def ld_compress_topk(grad: torch.Tensor, residual: torch.Tensor, seg_off, seg_k,
                      out_idx: Optional[torch.Tensor] = None, out_val: Optional[torch.Tensor] = None,
-                     workspace: Optional[torch.Tensor] = None, stream=None
-                     ) -> Tuple[torch.Tensor, torch.Tensor]:
+                     workspace: Optional[torch.Tensor] = None, stream=None,
+                     strategy: int = LD_COMPRESS_AUTO) -> Tuple[torch.Tensor, torch.Tensor]:
     """Per-segment top-k with error feedback; `residual` is updated in place.
     Returns (out_idx int32[K], out_val float32[K])."""
     lib = load()
@@ -123,10 +126,11 @@ def ld_compress_topk(grad: torch.Tensor, residual: torch.Tensor, seg_off, seg_k,
     if workspace is None:
         workspace = torch.empty(max(1, int(lib.ld_compress_topk_workspace(n_seg, _hp(seg_off)))),
                                 dtype=torch.uint8, device=grad.device)
-    st = lib.ld_compress_topk(_dev(grad, torch.float32, "grad"), _dev(residual, torch.float32, "residual"),
-                              _hp(seg_off), _hp(seg_k), n_seg,
-                              _dev(out_idx, torch.int32, "out_idx"), _dev(out_val, torch.float32, "out_val"),
-                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    st = lib.ld_compress_topk_strategy(
+        _dev(grad, torch.float32, "grad"), _dev(residual, torch.float32, "residual"),
+        _hp(seg_off), _hp(seg_k), n_seg,
+        _dev(out_idx, torch.int32, "out_idx"), _dev(out_val, torch.float32, "out_val"),
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream), int(strategy))
     _check("ld_compress_topk", st)
     return out_idx, out_val
 

@@ -25,16 +25,21 @@ def to_gpu(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
-def check_compress(g, r, seg_off, seg_k, select=True, tag=""):
-    """Runs one compress call on both sides; returns (idx, val, r_new) of the oracle."""
+def check_compress(g, r, seg_off, seg_k, select=True, tag="",
+                   strategies=(ld.LD_COMPRESS_AUTO, ld.LD_COMPRESS_FULL)):
+    """Runs one compress call per strategy on the GPU and once on the oracle;
+    returns (idx, val, r_new) of the oracle."""
     print(f"[compress] {tag} n={len(g)} n_seg={len(seg_k)}", flush=True)
-    r_gpu = to_gpu(r)
-    idx, val = ld.ld_compress_topk(to_gpu(g), r_gpu, seg_off, seg_k)
-    torch.cuda.synchronize()
     oi, ov, orr = oracle.topk_ef(g, r, seg_off, seg_k, select=select)
-    np.testing.assert_array_equal(idx.cpu().numpy(), oi, err_msg=f"idx {tag}")
-    np.testing.assert_array_equal(bits(val.cpu().numpy()), bits(ov), err_msg=f"val {tag}")
-    np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(orr), err_msg=f"residual {tag}")
+    g_gpu = to_gpu(g)
+    for strategy in strategies:
+        r_gpu = to_gpu(r)
+        idx, val = ld.ld_compress_topk(g_gpu, r_gpu, seg_off, seg_k, strategy=strategy)
+        torch.cuda.synchronize()
+        tg = f"{tag} strategy={strategy}"
+        np.testing.assert_array_equal(idx.cpu().numpy(), oi, err_msg=f"idx {tg}")
+        np.testing.assert_array_equal(bits(val.cpu().numpy()), bits(ov), err_msg=f"val {tg}")
+        np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(orr), err_msg=f"residual {tg}")
     return oi, ov, orr
 
 
