@@ -230,6 +230,41 @@ __device__ uint32_t block_select(const uint32_t (&key)[ITEMS], uint32_t valid_ma
     return prefix;
 }
 
+// The keys at ranks rank_a >= rank_b (1 = largest), each rounded DOWN to a
+// multiple of 2^kShift2: two radix levels resolve the top 22 bits, which is all
+// an estimate needs. Both ranks share one pass over the keys per level.
+template <int NT, int ITEMS>
+__device__ void block_select2(const uint32_t (&key)[ITEMS], uint32_t valid_mask, uint32_t rank_a,
+                              uint32_t rank_b, uint32_t* lh_a, uint32_t* lh_b, uint32_t* sh, uint32_t* res,
+                              uint32_t& out_a, uint32_t& out_b) {
+    uint32_t pa = 0, pb = 0, ka = rank_a, kb = rank_b;
+#pragma unroll 1
+    for (int level = 0; level < 2; ++level) {
+        const int match_shift = (level == 0) ? 31 : kShift1;
+        const int digit_shift = (level == 0) ? kShift1 : kShift2;
+        const bool same = (pa == pb);
+        for (int b = threadIdx.x; b < kBins; b += NT) { lh_a[b] = 0; lh_b[b] = 0; }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            if (!((valid_mask >> i) & 1u)) continue;
+            const uint32_t d = (key[i] >> digit_shift) & 0x7FFu;
+            if ((key[i] >> match_shift) == (pa >> match_shift)) atomicAdd(&lh_a[d], 1u);
+            if (!same && (key[i] >> match_shift) == (pb >> match_shift)) atomicAdd(&lh_b[d], 1u);
+        }
+        __syncthreads();
+        find_bin<NT, false>(lh_a, ka, sh, res);
+        find_bin<NT, false>(same ? lh_a : lh_b, kb, sh, res + 2);
+        pa |= res[0] << digit_shift;
+        ka = res[1];
+        pb |= res[2] << digit_shift;
+        kb = res[3];
+        __syncthreads();
+    }
+    out_a = pa;
+    out_b = pb;
+}
+
 __device__ __forceinline__ uint32_t mbcnt(uint64_t mask) {  // set bits of `mask` below this lane
     return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
                                      __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
@@ -309,9 +344,9 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x) {
 
 __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__ g,
                                                        const float* __restrict__ r, PrepBatch pb, Ctx c) {
-    __shared__ uint32_t lh[kBins];
+    __shared__ uint32_t lh[kBins], lh2[kBins];
     __shared__ uint32_t sh[kPrepThreads / LD_WAVE];
-    __shared__ uint32_t res[2];
+    __shared__ uint32_t res[4];
     __shared__ long long sums[2];
     const int j = blockIdx.x;
     const int s = pb.first + j;
@@ -369,10 +404,13 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
                 valid |= 1u << i;
             }
         }
-        uint32_t ties;
+        // Sample ranks (1 = largest). The estimates are rounded down to 2^kShift2, which only
+        // adds a few candidates.
         if (whole) {
-            // the sample is the segment: tau is the exact threshold, bins of width 1
-            tau = block_select<kPrepThreads, kSampleItems>(key, valid, static_cast<uint32_t>(k), lh, sh, res, &ties);
+            // the sample is the segment: tau is (just below) the exact threshold; bins of width 1
+            uint32_t unused;
+            block_select2<kPrepThreads, kSampleItems>(key, valid, static_cast<uint32_t>(k), static_cast<uint32_t>(k),
+                                                      lh, lh2, sh, res, tau, unused);
         } else {
             // expected sample hits a = k * kSample / ns. Candidates: sample rank x with x = a + z*sqrt(x),
             // so that fewer than k elements at or above tau is a z-sigma event.
@@ -383,13 +421,13 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
                 tau = 0;  // k too large for an estimate: everything is a candidate
                 binsh = kShift1;
             } else {
-                tau = block_select<kPrepThreads, kSampleItems>(key, valid, rank, lh, sh, res, &ties);
                 // bins span [tau, hi] where hi is the sample key at rank a - z*sqrt(a): the k-th
                 // largest key lies below it, in a fine bin, except in a z-sigma event
                 const float lo_rank = a - kSampleZ * sqrtf(a);
                 const uint32_t rank_hi = lo_rank > 1.0f ? static_cast<uint32_t>(lo_rank) : 1u;
-                const uint32_t hi = block_select<kPrepThreads, kSampleItems>(key, valid, rank_hi, lh, sh, res, &ties);
-                const uint32_t range = hi - tau;
+                uint32_t hi;
+                block_select2<kPrepThreads, kSampleItems>(key, valid, rank, rank_hi, lh, lh2, sh, res, tau, hi);
+                const uint32_t range = (hi | ((1u << kShift2) - 1u)) - tau;
                 while ((range >> binsh) > static_cast<uint32_t>(kTopBin - 1)) ++binsh;
             }
         }
@@ -494,34 +532,70 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
 
 // ------------------------------------------------- passes over the candidates
 
-// Visits, in index order, every candidate of one tile in batches of 64 (one per
-// lane). f(have, val, local) is called by all lanes of the wave together; `local`
-// is the element's offset inside the tile. A tile whose slot overflowed is read
-// back from the residual and filtered with the same test k_main applied.
-template <class F>
-__device__ __forceinline__ void for_each_candidate(const Ctx& c, const float* __restrict__ r, int32_t tile,
-                                                   int64_t tbase, int64_t seg_lo, int64_t seg_hi, uint32_t tau,
-                                                   F&& f) {
+// A wave of a small pass owns kTilesPerWave consecutive tiles of its group. For
+// each live tile, in order: begin(tl); then item(have, val, local) for batches of
+// 64 candidates (one per lane, index order, called by all lanes together; `local`
+// is the element's offset inside the tile); then end(tl). The slots of kBatch
+// tiles are fetched together so that several loads are in flight per lane. A tile
+// whose slot overflowed is read back from the residual and filtered with the same
+// test k_main applied.
+constexpr int kTilesPerWave = kTilesPerGroup / kWaves;
+constexpr int kBatch = 4;
+
+template <bool IDX, class Begin, class Item, class End>
+__device__ __forceinline__ void wave_tiles(const Ctx& c, const float* __restrict__ r, const GroupRange& gr,
+                                           int32_t group, uint32_t tau, Begin&& begin, Item&& item, End&& end) {
     const int lane = ld_lane();
-    const uint32_t cnt = c.cnt[tile];
-    if (cnt != kOverflow) {
-        const float* val = c.cval + static_cast<int64_t>(tile) * kSlot;
-        const uint16_t* idx = c.cidx + static_cast<int64_t>(tile) * kSlot;
-        for (uint32_t i0 = 0; i0 < cnt; i0 += 2 * LD_WAVE) {
-            const bool h0 = i0 + lane < cnt, h1 = i0 + LD_WAVE + lane < cnt;
-            const float v0 = h0 ? val[i0 + lane] : 0.0f;
-            const float v1 = h1 ? val[i0 + LD_WAVE + lane] : 0.0f;
-            const uint32_t x0 = h0 ? idx[i0 + lane] : 0u;
-            const uint32_t x1 = h1 ? idx[i0 + LD_WAVE + lane] : 0u;
-            f(h0, v0, x0);
-            if (i0 + LD_WAVE < cnt) f(h1, v1, x1);
+    const int w = threadIdx.x >> 6;
+    const int tl0 = w * kTilesPerWave;
+    const int32_t tile0 = group * kTilesPerGroup + tl0;
+    const int64_t tbase0 = gr.base + static_cast<int64_t>(tl0) * kTile;
+    int live = 0;
+    if (tbase0 < gr.hi) {
+        const int64_t nt = (gr.hi - tbase0 + kTile - 1) / kTile;
+        live = nt < kTilesPerWave ? static_cast<int>(nt) : kTilesPerWave;
+    }
+    const uint32_t mycnt = lane < live ? c.cnt[tile0 + lane] : 0u;
+    for (int i0 = 0; i0 < live; i0 += kBatch) {
+        uint32_t cn[kBatch], x0[kBatch], x1[kBatch];
+        float v0[kBatch], v1[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            cn[u] = (i0 + u < live) ? static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), i0 + u, LD_WAVE)) : 0u;
+            const uint32_t n = cn[u] == kOverflow ? 0u : cn[u];
+            const int64_t slot = static_cast<int64_t>(tile0 + i0 + u) * kSlot;
+            const bool h0 = static_cast<uint32_t>(lane) < n, h1 = static_cast<uint32_t>(lane + LD_WAVE) < n;
+            v0[u] = h0 ? c.cval[slot + lane] : 0.0f;
+            v1[u] = h1 ? c.cval[slot + LD_WAVE + lane] : 0.0f;
+            x0[u] = (IDX && h0) ? c.cidx[slot + lane] : 0u;
+            x1[u] = (IDX && h1) ? c.cidx[slot + LD_WAVE + lane] : 0u;
         }
-    } else {
-        for (int32_t l0 = 0; l0 < kTile; l0 += LD_WAVE) {
-            const int64_t e = tbase + l0 + lane;
-            const bool in = e >= seg_lo && e < seg_hi;
-            const float v = in ? r[e] : 0.0f;
-            f(in && ld_key(v) >= tau, v, static_cast<uint32_t>(l0 + lane));
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            if (i0 + u >= live) break;
+            const int tl = tl0 + i0 + u;
+            begin(tl);
+            if (cn[u] != kOverflow) {
+                const uint32_t n = cn[u];
+                if (n > 0) item(static_cast<uint32_t>(lane) < n, v0[u], x0[u]);
+                if (n > LD_WAVE) item(static_cast<uint32_t>(lane + LD_WAVE) < n, v1[u], x1[u]);
+                const int64_t slot = static_cast<int64_t>(tile0 + i0 + u) * kSlot;
+                for (uint32_t b0 = 2 * LD_WAVE; b0 < n; b0 += LD_WAVE) {
+                    const bool h = b0 + lane < n;
+                    const float v = h ? c.cval[slot + b0 + lane] : 0.0f;
+                    const uint32_t x = (IDX && h) ? c.cidx[slot + b0 + lane] : 0u;
+                    item(h, v, x);
+                }
+            } else {
+                const int64_t tbase = gr.base + static_cast<int64_t>(tl) * kTile;
+                for (int32_t l0 = 0; l0 < kTile; l0 += LD_WAVE) {
+                    const int64_t e = tbase + l0 + lane;
+                    const bool in = e >= gr.lo && e < gr.hi;
+                    const float v = in ? r[e] : 0.0f;
+                    item(in && ld_key(v) >= tau, v, static_cast<uint32_t>(l0 + lane));
+                }
+            }
+            end(tl);
         }
     }
 }
@@ -539,16 +613,12 @@ __global__ __launch_bounds__(kThreads) void k_hist(const float* __restrict__ r, 
     const uint32_t tau = st->tau, binsh = st->sh;
     for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
     __syncthreads();
-    const int w = threadIdx.x >> 6;
-    for (int i = 0; i < kTilesPerGroup / kWaves; ++i) {
-        const int tl = w * (kTilesPerGroup / kWaves) + i;
-        const int64_t tbase = gr.base + static_cast<int64_t>(tl) * kTile;
-        if (tbase >= gr.hi) break;
-        for_each_candidate(c, r, blockIdx.x * kTilesPerGroup + tl, tbase, gr.lo, gr.hi, tau,
-                           [&](bool have, float v, uint32_t) {
-                               if (have) atomicAdd(&lh[fine_bin(ld_key(v), tau, binsh)], 1u);
-                           });
-    }
+    wave_tiles<false>(
+        c, r, gr, blockIdx.x, tau, [](int) {},
+        [&](bool have, float v, uint32_t) {
+            if (have) atomicAdd(&lh[fine_bin(ld_key(v), tau, binsh)], 1u);
+        },
+        [](int) {});
     __syncthreads();
     uint32_t* h = c.hist + static_cast<int64_t>(gr.seg) * kBins;
     flush_hist(h, lh);
@@ -587,37 +657,38 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     const int w = threadIdx.x >> 6;
     uint32_t* gkey = c.gkey + static_cast<int64_t>(gr.seg) * kGatherCap;
     int32_t* gtile = c.gtile + static_cast<int64_t>(gr.seg) * kGatherCap;
-    uint32_t wave_gt = 0;
-    for (int i = 0; i < kTilesPerGroup / kWaves; ++i) {
-        const int tl = w * (kTilesPerGroup / kWaves) + i;
-        const int32_t tile = blockIdx.x * kTilesPerGroup + tl;
-        const int64_t tbase = gr.base + static_cast<int64_t>(tl) * kTile;
-        uint32_t gt = 0;
-        if (tbase < gr.hi) {
-            for_each_candidate(c, r, tile, tbase, gr.lo, gr.hi, tau, [&](bool have, float v, uint32_t) {
-                const uint32_t key = ld_key(v);
-                const uint32_t bin = have ? fine_bin(key, tau, binsh) : 0u;
-                gt += __popcll(__ballot(have && bin > b1));
-                const bool in = have && bin == b1;
-                const uint64_t min_ = __ballot(in);
-                if (min_) {
-                    uint32_t base = 0;
-                    if (lane == 0) base = atomicAdd(&st->gcount, static_cast<uint32_t>(__popcll(min_)));
-                    base = __shfl(base, 0, LD_WAVE);
-                    const uint32_t pos = base + mbcnt(min_);
-                    if (in && pos < static_cast<uint32_t>(kGatherCap)) {
-                        gkey[pos] = key;
-                        gtile[pos] = tile;
-                    }
+    uint32_t wave_gt = 0, gt = 0;
+    int32_t tile_of_item = 0;
+    wave_tiles<false>(
+        c, r, gr, blockIdx.x, tau,
+        [&](int tl) {
+            gt = 0;
+            tile_of_item = blockIdx.x * kTilesPerGroup + tl;
+        },
+        [&](bool have, float v, uint32_t) {
+            const uint32_t key = ld_key(v);
+            const uint32_t bin = have ? fine_bin(key, tau, binsh) : 0u;
+            gt += __popcll(__ballot(have && bin > b1));
+            const bool in = have && bin == b1;
+            const uint64_t min_ = __ballot(in);
+            if (min_) {
+                uint32_t base = 0;
+                if (lane == 0) base = atomicAdd(&st->gcount, static_cast<uint32_t>(__popcll(min_)));
+                base = __shfl(base, 0, LD_WAVE);
+                const uint32_t pos = base + mbcnt(min_);
+                if (in && pos < static_cast<uint32_t>(kGatherCap)) {
+                    gkey[pos] = key;
+                    gtile[pos] = tile_of_item;
                 }
-            });
-        }
-        if (lane == 0) {
-            c.tile_gt[tile] = gt;
-            c.tile_eq[tile] = 0;
-        }
-        wave_gt += gt;
-    }
+            }
+        },
+        [&](int tl) {
+            if (lane == 0) {
+                c.tile_gt[blockIdx.x * kTilesPerGroup + tl] = gt;
+                c.tile_eq[blockIdx.x * kTilesPerGroup + tl] = 0;
+            }
+            wave_gt += gt;
+        });
     if (lane == 0) wsum[w] = wave_gt;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -707,31 +778,34 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
         tile_eqb[lane] = eq_before;
     }
     __syncthreads();
-    for (int i = 0; i < kTilesPerGroup / kWaves; ++i) {
-        const int tl = w * (kTilesPerGroup / kWaves) + i;
-        const int64_t tbase = gr.base + static_cast<int64_t>(tl) * kTile;
-        if (tbase >= gr.hi) break;
-        uint32_t run_out = tile_out[tl];  // records of the segment emitted before this point
-        uint32_t run_eq = tile_eqb[tl];   // ties seen before this point
-        for_each_candidate(c, r, blockIdx.x * kTilesPerGroup + tl, tbase, gr.lo, gr.hi, tau,
-                           [&](bool have, float v, uint32_t local) {
-                               const uint32_t key = ld_key(v);
-                               const bool is_gt = have && key > T;
-                               const bool is_eq = have && key == T;
-                               const uint64_t mg = __ballot(is_gt), me = __ballot(is_eq);
-                               const uint32_t eq_rank = run_eq + mbcnt(me);
-                               if (is_gt || (is_eq && eq_rank < m)) {
-                                   const int64_t pos = gr.out0 + run_out + mbcnt(mg) + (umin(eq_rank, m) - umin(run_eq, m));
-                                   const int64_t e = tbase + local;
-                                   out_idx[pos] = static_cast<int32_t>(e);
-                                   out_val[pos] = v;
-                                   r[e] = 0.0f;
-                               }
-                               const uint32_t eq_end = run_eq + __popcll(me);
-                               run_out += __popcll(mg) + (umin(eq_end, m) - umin(run_eq, m));
-                               run_eq = eq_end;
-                           });
-    }
+    uint32_t run_out = 0;  // records of the segment emitted before this point
+    uint32_t run_eq = 0;   // ties seen before this point
+    int64_t tbase = 0;
+    wave_tiles<true>(
+        c, r, gr, blockIdx.x, tau,
+        [&](int tl) {
+            run_out = tile_out[tl];
+            run_eq = tile_eqb[tl];
+            tbase = gr.base + static_cast<int64_t>(tl) * kTile;
+        },
+        [&](bool have, float v, uint32_t local) {
+            const uint32_t key = ld_key(v);
+            const bool is_gt = have && key > T;
+            const bool is_eq = have && key == T;
+            const uint64_t mg = __ballot(is_gt), me = __ballot(is_eq);
+            const uint32_t eq_rank = run_eq + mbcnt(me);
+            if (is_gt || (is_eq && eq_rank < m)) {
+                const int64_t pos = gr.out0 + run_out + mbcnt(mg) + (umin(eq_rank, m) - umin(run_eq, m));
+                const int64_t e = tbase + local;
+                out_idx[pos] = static_cast<int32_t>(e);
+                out_val[pos] = v;
+                r[e] = 0.0f;
+            }
+            const uint32_t eq_end = run_eq + __popcll(me);
+            run_out += __popcll(mg) + (umin(eq_end, m) - umin(run_eq, m));
+            run_eq = eq_end;
+        },
+        [](int) {});
 }
 
 // ------------------------------------------ full-segment path (kModeFull only)
