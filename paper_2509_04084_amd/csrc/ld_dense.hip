@@ -98,17 +98,27 @@ __device__ __forceinline__ void adam_step(float& w, float& m, float& v, float g,
 }
 
 constexpr int kAdamThreads = 256;
-constexpr int kAdamVec = 8;  // elements per thread per step: one 16-byte bf16 load
+constexpr int kAdamVec = 8;                                // elements per thread: one 16-byte bf16 load per step
+constexpr int kAdamBlockElems = kAdamThreads * kAdamVec;   // 2048 elements per workgroup
 
+// Replays steps [t0, t0 + WT) of the window (those below a.W) on 8 consecutive
+// elements per thread. One workgroup per 2048 elements, in address order; all
+// gradient loads of the WT steps are issued before the first is used.
+template <int WT>
 __global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, float* __restrict__ m,
-                                                       float* __restrict__ v, int64_t n, AdamArgs a) {
-    const int64_t nvec = n / kAdamVec;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kAdamThreads;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kAdamThreads + threadIdx.x; i < nvec; i += stride) {
+                                                       float* __restrict__ v, int64_t n, AdamArgs a, int t0) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kAdamThreads + threadIdx.x;  // 8-element vector index
+    const int64_t e0 = i * kAdamVec;
+    if (e0 + kAdamVec <= n) {
         ld_f32x4 wv[2], mv[2], vv[2];
+        ld_u32x4 gq[WT];
         ld_f32x4* w4 = reinterpret_cast<ld_f32x4*>(w) + i * 2;
         ld_f32x4* m4 = reinterpret_cast<ld_f32x4*>(m) + i * 2;
         ld_f32x4* v4 = reinterpret_cast<ld_f32x4*>(v) + i * 2;
+#pragma unroll
+        for (int t = 0; t < WT; ++t)
+            gq[t] = (t0 + t < a.W) ? ld_nt_load(reinterpret_cast<const ld_u32x4*>(a.grad[t0 + t]) + i)
+                                   : ld_u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             wv[h] = ld_nt_load(w4 + h);
@@ -118,15 +128,17 @@ __global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, fl
         float ww[8] = {wv[0].x, wv[0].y, wv[0].z, wv[0].w, wv[1].x, wv[1].y, wv[1].z, wv[1].w};
         float mm[8] = {mv[0].x, mv[0].y, mv[0].z, mv[0].w, mv[1].x, mv[1].y, mv[1].z, mv[1].w};
         float v8[8] = {vv[0].x, vv[0].y, vv[0].z, vv[0].w, vv[1].x, vv[1].y, vv[1].z, vv[1].w};
-        for (int t = 0; t < a.W; ++t) {
-            const ld_u32x4 gq = ld_nt_load(reinterpret_cast<const ld_u32x4*>(a.grad[t]) + i);
-            const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
-            const float lr_bc1 = a.lr_over_bc1[t], ibc2 = a.inv_bc2[t];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t half = (e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu);
-                adam_step(ww[e], mm[e], v8[e], bf16_widen(half), a.beta1, a.one_m_beta1, a.beta2,
-                          a.one_m_beta2, a.eps, lr_bc1, ibc2);
+        for (int t = 0; t < WT; ++t) {
+            if (t0 + t < a.W) {
+                const uint32_t gw[4] = {gq[t].x, gq[t].y, gq[t].z, gq[t].w};
+                const float lr_bc1 = a.lr_over_bc1[t0 + t], ibc2 = a.inv_bc2[t0 + t];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t half = (e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu);
+                    adam_step(ww[e], mm[e], v8[e], bf16_widen(half), a.beta1, a.one_m_beta1, a.beta2,
+                              a.one_m_beta2, a.eps, lr_bc1, ibc2);
+                }
             }
         }
 #pragma unroll
@@ -135,18 +147,17 @@ __global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, fl
             ld_nt_store(ld_f32x4{mm[4 * h], mm[4 * h + 1], mm[4 * h + 2], mm[4 * h + 3]}, m4 + h);
             ld_nt_store(ld_f32x4{v8[4 * h], v8[4 * h + 1], v8[4 * h + 2], v8[4 * h + 3]}, v4 + h);
         }
-    }
-    // ragged tail (< 8 elements), one thread each
-    const int64_t tail0 = nvec * kAdamVec;
-    if (blockIdx.x == 0 && tail0 + threadIdx.x < n) {
-        const int64_t i = tail0 + threadIdx.x;
-        float ww = w[i], mm = m[i], v1 = v[i];
-        for (int t = 0; t < a.W; ++t)
-            adam_step(ww, mm, v1, bf16_widen(a.grad[t][i]), a.beta1, a.one_m_beta1, a.beta2,
-                      a.one_m_beta2, a.eps, a.lr_over_bc1[t], a.inv_bc2[t]);
-        w[i] = ww;
-        m[i] = mm;
-        v[i] = v1;
+    } else {
+        // ragged tail: fewer than 8 elements left for this thread
+        for (int64_t e = e0; e < n; ++e) {
+            float ww = w[e], mm = m[e], v1 = v[e];
+            for (int t = t0; t < t0 + WT && t < a.W; ++t)
+                adam_step(ww, mm, v1, bf16_widen(a.grad[t][e]), a.beta1, a.one_m_beta1, a.beta2,
+                          a.one_m_beta2, a.eps, a.lr_over_bc1[t], a.inv_bc2[t]);
+            w[e] = ww;
+            m[e] = mm;
+            v[e] = v1;
+        }
     }
 }
 
@@ -238,12 +249,20 @@ extern "C" ld_status ld_merge_dense_adam(float* w, float* m, float* v, int64_t n
     a.one_m_beta2 = 1.0f - beta2;
     a.eps = eps;
     a.W = W;
-    const int64_t nvec = n / kAdamVec;
-    int64_t blocks = (nvec + kAdamThreads - 1) / kAdamThreads;
-    const int64_t cap = 256 * 64;  // grid-stride beyond 64 blocks per CU
-    if (blocks > cap) blocks = cap;
-    if (blocks < 1) blocks = 1;
-    k_adam<<<dim3(static_cast<uint32_t>(blocks)), dim3(kAdamThreads), 0,
-             static_cast<hipStream_t>(stream)>>>(w, m, v, n, a);
-    return ld_launch_status();
+    const int64_t blocks = (n + kAdamBlockElems - 1) / kAdamBlockElems;
+    if (blocks > INT32_MAX) return LD_ERR_RANGE;
+    const dim3 grid(static_cast<uint32_t>(blocks)), block(kAdamThreads);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // steps are fused four (or eight) at a time; the state round-trips through fp32
+    // memory between passes, which is exactly what it does between two calls
+    int t0 = 0;
+    while (t0 < W) {
+        const int left = W - t0;
+        if (left > 4) { k_adam<8><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 8; }
+        else if (left > 2) { k_adam<4><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 4; }
+        else if (left > 1) { k_adam<2><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 2; }
+        else { k_adam<1><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 1; }
+        if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
+    }
+    return LD_OK;
 }

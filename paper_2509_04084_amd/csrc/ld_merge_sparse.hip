@@ -38,7 +38,29 @@ __global__ __launch_bounds__(256) void k_partition(DiffTable tb, int64_t n, int3
     int64_t target = static_cast<int64_t>(b) * kSub;
     if (target > n) target = n;
     const int32_t* __restrict__ idx = tb.idx[t];
-    int32_t lo = 0, hi = tb.K[t];
+    const int32_t K = tb.K[t];
+    // Records are spread almost evenly over [0, n): start from the proportional
+    // position, gallop to a bracket [lo, hi] that holds the answer, then bisect.
+    int32_t guess = static_cast<int32_t>(static_cast<int64_t>(K) * target / (n > 0 ? n : 1));
+    if (guess > K) guess = K;
+    int32_t lo, hi, step = 32;
+    if (guess < K && static_cast<int64_t>(idx[guess]) < target) {
+        lo = guess + 1;
+        hi = (K - lo < step) ? K : lo + step;
+        while (hi < K && static_cast<int64_t>(idx[hi]) < target) {
+            lo = hi + 1;
+            step *= 2;
+            hi = (K - lo < step) ? K : lo + step;
+        }
+    } else {
+        hi = guess;
+        lo = (hi < step) ? 0 : hi - step;
+        while (lo > 0 && static_cast<int64_t>(idx[lo]) >= target) {
+            hi = lo;
+            step *= 2;
+            lo = (hi < step) ? 0 : hi - step;
+        }
+    }
     while (lo < hi) {
         const int32_t mid = lo + ((hi - lo) >> 1);
         if (static_cast<int64_t>(idx[mid]) < target) lo = mid + 1; else hi = mid;
