@@ -29,43 +29,39 @@ struct DiffTable {
     int32_t K[kGroupMax];
 };
 
-// tab[t*(nsub+1) + b] = number of records of diff t with idx < min(n, b*kSub).
-__global__ __launch_bounds__(256) void k_partition(DiffTable tb, int64_t n, int32_t nsub,
-                                                   int32_t* __restrict__ tab) {
-    const int32_t b = blockIdx.x * 256 + threadIdx.x;
-    const int t = blockIdx.y;
-    if (b > nsub) return;
-    int64_t target = static_cast<int64_t>(b) * kSub;
-    if (target > n) target = n;
-    const int32_t* __restrict__ idx = tb.idx[t];
-    const int32_t K = tb.K[t];
-    // Records are spread almost evenly over [0, n): start from the proportional
-    // position, gallop to a bracket [lo, hi] that holds the answer, then bisect.
-    int32_t guess = static_cast<int32_t>(static_cast<int64_t>(K) * target / (n > 0 ? n : 1));
-    if (guess > K) guess = K;
-    int32_t lo, hi, step = 32;
-    if (guess < K && static_cast<int64_t>(idx[guess]) < target) {
-        lo = guess + 1;
-        hi = (K - lo < step) ? K : lo + step;
-        while (hi < K && static_cast<int64_t>(idx[hi]) < target) {
-            lo = hi + 1;
-            step *= 2;
-            hi = (K - lo < step) ? K : lo + step;
-        }
-    } else {
-        hi = guess;
-        lo = (hi < step) ? 0 : hi - step;
-        while (lo > 0 && static_cast<int64_t>(idx[lo]) >= target) {
-            hi = lo;
-            step *= 2;
-            lo = (hi < step) ? 0 : hi - step;
-        }
-    }
+__device__ __forceinline__ int32_t lower_bound_idx(const int32_t* __restrict__ idx, int32_t lo, int32_t hi,
+                                                   int64_t target) {
     while (lo < hi) {
         const int32_t mid = lo + ((hi - lo) >> 1);
         if (static_cast<int64_t>(idx[mid]) < target) lo = mid + 1; else hi = mid;
     }
-    tab[static_cast<int64_t>(t) * (nsub + 1) + b] = lo;
+    return lo;
+}
+
+// tab[t*(nsub+1) + b] = number of records of diff t with idx < min(n, b*kSub).
+// A workgroup covers 256 consecutive boundaries of one diff: two threads bracket
+// the whole run with full searches, then every thread bisects inside the bracket
+// (a few KB of indices that the workgroup shares through the cache).
+__global__ __launch_bounds__(256) void k_partition(DiffTable tb, int64_t n, int32_t nsub,
+                                                   int32_t* __restrict__ tab) {
+    __shared__ int32_t bracket[2];
+    const int32_t b0 = blockIdx.x * 256;
+    const int32_t b = b0 + threadIdx.x;
+    const int t = blockIdx.y;
+    const int32_t* __restrict__ idx = tb.idx[t];
+    const int32_t K = tb.K[t];
+    if (threadIdx.x < 2) {
+        int32_t bb = threadIdx.x == 0 ? b0 : b0 + 255;
+        if (bb > nsub) bb = nsub;
+        int64_t target = static_cast<int64_t>(bb) * kSub;
+        if (target > n) target = n;
+        bracket[threadIdx.x] = lower_bound_idx(idx, 0, K, target);
+    }
+    __syncthreads();
+    if (b > nsub) return;
+    int64_t target = static_cast<int64_t>(b) * kSub;
+    if (target > n) target = n;
+    tab[static_cast<int64_t>(t) * (nsub + 1) + b] = lower_bound_idx(idx, bracket[0], bracket[1], target);
 }
 
 __device__ __forceinline__ void apply_record(float* tile, int32_t local, float val, float lr) {
