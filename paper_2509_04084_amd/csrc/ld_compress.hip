@@ -8,33 +8,41 @@
 // Design: ONE streaming pass over gradient and residual, then three small passes
 // over a candidate set of about 1.7 * k elements.
 //
-//   k_prep    one workgroup per segment: writes the segment's tables, and from a
-//             16K-element sample of |r+g| estimates a candidate threshold tau (the
-//             sample key at a rank high enough that, with overwhelming probability,
-//             at least k elements of the segment lie at or above it; exact when the
-//             whole segment fits in the sample) and the width of the fine bins
-//             that the later passes lay over the keys above tau.
-//   k_main    a = r + g -> residual: 12 bytes per element, the only full pass. One
-//             workgroup per 4096-element tile, tiles in address order so that the
-//             workgroups in flight cover one contiguous window of HBM. Elements with
-//             key >= tau go, in index order, into the tile's candidate slot.
-//   k_hist    histogram of the candidates over 2048 fine bins; the workgroup that
-//             finishes a segment last finds the bin b holding the k-th largest key.
+//   k_upload  segment tables (kernel arguments -> workspace).
+//   k_prep    one workgroup per segment: from a 16K-element sample of |r+g| it
+//             estimates three keys: a candidate threshold tau (the sample key at a
+//             rank high enough that, with overwhelming probability, at least k
+//             elements of the segment lie at or above it), the likeliest threshold
+//             T_est (the sample key at the rank that corresponds to k), and the top
+//             of the fine bins that the later passes lay over the keys above tau.
+//             When the whole segment fits in the sample the three are exact.
+//   k_main    the only full pass, 12 bytes per element. One workgroup per
+//             4096-element tile, tiles in address order so that the workgroups in
+//             flight cover one contiguous window of HBM. Elements with key >= tau
+//             go, in index order, into the tile's candidate slot. The residual is
+//             written as if T_est were the threshold: +0 where key >= T_est, r + g
+//             elsewhere - so that the scattered repair writes of the last pass touch
+//             only the elements between T_est and the true threshold (a few percent
+//             of k) instead of all k selected positions.
+//   k_hist    histogram of the candidates over 2048 fine bins; k_bin (one workgroup
+//             per segment) finds the bin b holding the k-th largest key.
 //   k_gather  per tile: #candidates in bins above b; the (few) keys inside bin b are
-//             gathered per segment; the last workgroup selects the exact threshold T
-//             and tie count among them, fixes the per-tile counts up, and scans
-//             them into output offsets.
-//   k_emit    ordered emission of (idx, val); residual[idx] <- +0.
+//             gathered per segment. k_select (one workgroup per segment) selects the
+//             exact threshold T and tie count among them, fixes the per-tile counts
+//             up, and scans them into output offsets.
+//   k_emit    ordered emission of (idx, val); repairs the residual where the
+//             T_est guess and the true selection differ.
 //
-// The estimate can never make the result wrong, only slower:
-//   * a tile with more candidates than its slot holds is marked, and the later
-//     passes re-read that tile from the residual;
+// The estimates can never make the result wrong, only slower:
+//   * a tile with more candidates than its slot holds is marked, its residual is
+//     stored unzeroed, and the later passes re-read that tile from the residual;
 //   * a segment with fewer than k candidates, or with more keys in bin b than the
-//     gather list holds (massive ties), is handed to the k_full_* kernels: a plain
-//     three-level radix select over the whole segment.
-// Cross-workgroup hand-over inside a kernel uses a ticket counter with device-scope
-// release / acquire; only the small passes use it (the release costs an L2 write-
-// back, which a streaming kernel cannot afford per workgroup).
+//     gather list holds (massive ties), gets its residual restored from the slots
+//     and is handed to the k_full_* kernels: a plain three-level radix select over
+//     the whole segment.
+// Per-segment steps run as kernels of their own (a kernel boundary is the only
+// device-wide hand-over the normal path needs); the k_full_* kernels hand over
+// with a ticket counter (device-scope release / acquire).
 #include <math.h>
 
 #include "ld_common.h"
@@ -80,13 +88,13 @@ struct GroupDesc {
 struct SegState {       // 64 bytes
     uint32_t tau;       // candidate threshold (key); 0: every element, 0xFFFFFFFF: none
     uint32_t sh;        // fine bin of a candidate: min(kTopBin, (key - tau) >> sh)
-    uint32_t prefix;    // k_hist: threshold bin; k_gather: exact threshold T (k_full_*: radix prefix)
+    uint32_t test;      // guessed threshold T_est >= tau: k_main stores +0 where key >= T_est
+    uint32_t prefix;    // k_bin: threshold bin; k_select: exact threshold T (k_full_*: radix prefix)
     uint32_t krem;      // rank left inside prefix; finally the number of ties to keep
     uint32_t mode;      // kModeCand | kModeFull
     uint32_t gcount;    // keys gathered from the threshold bin
-    uint32_t done[2];   // tickets: k_hist, k_gather
     uint32_t fdone[4];  // tickets of the full-segment path: level 1, 2, 3, count
-    uint32_t pad[4];
+    uint32_t pad[5];
 };
 
 struct Ctx {
@@ -109,7 +117,7 @@ struct Ctx {
     int32_t n_group;
 };
 
-struct PrepBatch {
+struct UploadBatch {
     int32_t off[kSegPerLaunch + 1];
     int32_t k[kSegPerLaunch];
     int64_t out0;     // records before the first segment of the batch
@@ -117,7 +125,6 @@ struct PrepBatch {
     int32_t first;    // index of the batch's first segment
     int32_t count;
     int32_t n_seg;
-    int32_t no_estimate;  // LD_COMPRESS_FULL: collect no candidates, select over whole segments
 };
 
 __host__ __device__ inline int64_t align_down4(int64_t x) { return x & ~static_cast<int64_t>(3); }
@@ -230,39 +237,50 @@ __device__ uint32_t block_select(const uint32_t (&key)[ITEMS], uint32_t valid_ma
     return prefix;
 }
 
-// The keys at ranks rank_a >= rank_b (1 = largest), each rounded DOWN to a
-// multiple of 2^kShift2: two radix levels resolve the top 22 bits, which is all
-// an estimate needs. Both ranks share one pass over the keys per level.
-template <int NT, int ITEMS>
-__device__ void block_select2(const uint32_t (&key)[ITEMS], uint32_t valid_mask, uint32_t rank_a,
-                              uint32_t rank_b, uint32_t* lh_a, uint32_t* lh_b, uint32_t* sh, uint32_t* res,
-                              uint32_t& out_a, uint32_t& out_b) {
-    uint32_t pa = 0, pb = 0, ka = rank_a, kb = rank_b;
+// The keys at R ranks (1 = largest), each rounded DOWN to a multiple of
+// 2^kShift2: two radix levels resolve the top 22 bits, which is all an estimate
+// needs. The ranks share one pass over the keys per level; ranks whose prefixes
+// coincide share a histogram. `lh` holds R * kBins words, `res` 2 * R.
+template <int NT, int ITEMS, int R>
+__device__ void block_select_multi(const uint32_t (&key)[ITEMS], uint32_t valid_mask, const uint32_t (&rank)[R],
+                                   uint32_t* lh, uint32_t* sh, uint32_t* res, uint32_t (&out)[R]) {
+    uint32_t p[R], kr[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) { p[i] = 0; kr[i] = rank[i]; }
 #pragma unroll 1
     for (int level = 0; level < 2; ++level) {
         const int match_shift = (level == 0) ? 31 : kShift1;
         const int digit_shift = (level == 0) ? kShift1 : kShift2;
-        const bool same = (pa == pb);
-        for (int b = threadIdx.x; b < kBins; b += NT) { lh_a[b] = 0; lh_b[b] = 0; }
+        int own[R];  // the first rank with the same prefix: its histogram serves this one too
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            own[i] = i;
+#pragma unroll
+            for (int j = i - 1; j >= 0; --j)
+                if (p[j] == p[i]) own[i] = j;
+        }
+        for (int b = threadIdx.x; b < R * kBins; b += NT) lh[b] = 0;
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            if (!((valid_mask >> i) & 1u)) continue;
-            const uint32_t d = (key[i] >> digit_shift) & 0x7FFu;
-            if ((key[i] >> match_shift) == (pa >> match_shift)) atomicAdd(&lh_a[d], 1u);
-            if (!same && (key[i] >> match_shift) == (pb >> match_shift)) atomicAdd(&lh_b[d], 1u);
+        for (int q = 0; q < ITEMS; ++q) {
+            if (!((valid_mask >> q) & 1u)) continue;
+            const uint32_t d = (key[q] >> digit_shift) & 0x7FFu;
+#pragma unroll
+            for (int i = 0; i < R; ++i)
+                if (own[i] == i && (key[q] >> match_shift) == (p[i] >> match_shift)) atomicAdd(&lh[i * kBins + d], 1u);
         }
         __syncthreads();
-        find_bin<NT, false>(lh_a, ka, sh, res);
-        find_bin<NT, false>(same ? lh_a : lh_b, kb, sh, res + 2);
-        pa |= res[0] << digit_shift;
-        ka = res[1];
-        pb |= res[2] << digit_shift;
-        kb = res[3];
+#pragma unroll
+        for (int i = 0; i < R; ++i) find_bin<NT, false>(lh + own[i] * kBins, kr[i], sh, res + 2 * i);
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            p[i] |= res[2 * i] << digit_shift;
+            kr[i] = res[2 * i + 1];
+        }
         __syncthreads();
     }
-    out_a = pa;
-    out_b = pb;
+#pragma unroll
+    for (int i = 0; i < R; ++i) out[i] = p[i];
 }
 
 __device__ __forceinline__ uint32_t mbcnt(uint64_t mask) {  // set bits of `mask` below this lane
@@ -342,46 +360,44 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x) {
     return x;
 }
 
+// Segment tables of one batch: prefix sums over the batch entries before each one.
+__global__ __launch_bounds__(512) void k_upload(UploadBatch ub, Ctx c) {
+    const int j = threadIdx.x;
+    if (j >= ub.count) return;
+    int64_t ks = 0;
+    int32_t groups = 0;
+    for (int i = 0; i < j; ++i) {
+        groups += groups_of(ub.off[i], ub.off[i + 1]);
+        ks += ub.k[i];
+    }
+    const int s = ub.first + j;
+    c.desc[s] = SegDesc{ub.off[j], ub.out0 + ks, ub.k[j], ub.group0 + groups};
+    if (s == ub.n_seg - 1)
+        c.desc[s + 1] = SegDesc{ub.off[j + 1], ub.out0 + ks + ub.k[j], 0,
+                                ub.group0 + groups + groups_of(ub.off[j], ub.off[j + 1])};
+    if (s == 0) *c.fail_count = 0;
+}
+
 __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__ g,
-                                                       const float* __restrict__ r, PrepBatch pb, Ctx c) {
-    __shared__ uint32_t lh[kBins], lh2[kBins];
+                                                       const float* __restrict__ r, Ctx c,
+                                                       int32_t no_estimate) {
+    __shared__ uint32_t lh[3 * kBins];
     __shared__ uint32_t sh[kPrepThreads / LD_WAVE];
-    __shared__ uint32_t res[4];
-    __shared__ long long sums[2];
-    const int j = blockIdx.x;
-    const int s = pb.first + j;
-    // tables: prefix sums over the batch entries before this one
-    if (threadIdx.x == 0) { sums[0] = 0; sums[1] = 0; }
-    __syncthreads();
-    long long my_groups = 0, my_k = 0;
-    for (int i = threadIdx.x; i < j; i += kPrepThreads) {
-        my_groups += groups_of(pb.off[i], pb.off[i + 1]);
-        my_k += pb.k[i];
-    }
-    if (my_groups) atomicAdd(reinterpret_cast<unsigned long long*>(&sums[0]), static_cast<unsigned long long>(my_groups));
-    if (my_k) atomicAdd(reinterpret_cast<unsigned long long*>(&sums[1]), static_cast<unsigned long long>(my_k));
-    __syncthreads();
-    const int64_t off = pb.off[j], end = pb.off[j + 1];
-    const int32_t k = pb.k[j];
-    const int32_t group0 = pb.group0 + static_cast<int32_t>(sums[0]);
-    const int64_t out0 = pb.out0 + sums[1];
+    __shared__ uint32_t res[6];
+    const int s = blockIdx.x;
+    const SegDesc d = c.desc[s];
+    const int64_t off = d.off, end = c.desc[s + 1].off;
+    const int32_t k = d.k;
     const int32_t ngroup = groups_of(off, end);
-    if (threadIdx.x == 0) {
-        c.desc[s] = SegDesc{off, out0, k, group0};
-        if (s == pb.n_seg - 1) c.desc[s + 1] = SegDesc{end, out0 + k, 0, group0 + ngroup};
-        if (s == 0) *c.fail_count = 0;
-    }
     if (threadIdx.x < sizeof(SegState) / 4) reinterpret_cast<uint32_t*>(&c.state[s])[threadIdx.x] = 0;
     for (int b = threadIdx.x; b < kBins; b += kPrepThreads) c.hist[static_cast<int64_t>(s) * kBins + b] = 0;
     for (int32_t q = threadIdx.x; q < ngroup; q += kPrepThreads)
-        c.gdesc[group0 + q] = GroupDesc{align_down4(off) + static_cast<int64_t>(q) * kGroup, s, 0};
+        c.gdesc[d.group0 + q] = GroupDesc{align_down4(off) + static_cast<int64_t>(q) * kGroup, s, 0};
 
-    // candidate threshold and bin width from a sample of |r + g|
+    // candidate threshold, guessed threshold and bin width from a sample of |r + g|
     const int64_t ns = end - off;
-    uint32_t tau, binsh = 0;
-    if (k == 0 || pb.no_estimate) {
-        tau = 0xFFFFFFFFu;
-    } else {
+    uint32_t tau = 0xFFFFFFFFu, test = 0xFFFFFFFFu, binsh = 0;
+    if (k > 0 && !no_estimate) {
         uint32_t key[kSampleItems];
         uint32_t valid = 0;
         const bool whole = ns <= kSample;
@@ -404,37 +420,45 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
                 valid |= 1u << i;
             }
         }
-        // Sample ranks (1 = largest). The estimates are rounded down to 2^kShift2, which only
+        // Sample ranks (1 = largest). The selected keys are rounded down to 2^kShift2, which only
         // adds a few candidates.
+        uint32_t rank[3], sel[3];
         if (whole) {
-            // the sample is the segment: tau is (just below) the exact threshold; bins of width 1
-            uint32_t unused;
-            block_select2<kPrepThreads, kSampleItems>(key, valid, static_cast<uint32_t>(k), static_cast<uint32_t>(k),
-                                                      lh, lh2, sh, res, tau, unused);
+            // the sample is the segment: the exact threshold lies in [tau, tau + 2^kShift2); every key
+            // above that range is certainly selected; bins of width 1
+            rank[0] = rank[1] = rank[2] = static_cast<uint32_t>(k);
+            block_select_multi<kPrepThreads, kSampleItems, 3>(key, valid, rank, lh, sh, res, sel);
+            tau = sel[0];
+            test = tau + (1u << kShift2);
         } else {
             // expected sample hits a = k * kSample / ns. Candidates: sample rank x with x = a + z*sqrt(x),
             // so that fewer than k elements at or above tau is a z-sigma event.
             const float a = static_cast<float>(k) * (static_cast<float>(kSample) / static_cast<float>(ns));
             const float sq = 0.5f * (kSampleZ + sqrtf(kSampleZ * kSampleZ + 4.0f * a));
-            const uint32_t rank = static_cast<uint32_t>(sq * sq) + 2u;
-            if (rank >= static_cast<uint32_t>(kSample)) {
-                tau = 0;  // k too large for an estimate: everything is a candidate
+            rank[0] = static_cast<uint32_t>(sq * sq) + 2u;
+            if (rank[0] >= static_cast<uint32_t>(kSample)) {
+                tau = 0;  // k too large for an estimate: everything is a candidate, nothing is pre-zeroed
                 binsh = kShift1;
             } else {
                 // bins span [tau, hi] where hi is the sample key at rank a - z*sqrt(a): the k-th
                 // largest key lies below it, in a fine bin, except in a z-sigma event
                 const float lo_rank = a - kSampleZ * sqrtf(a);
-                const uint32_t rank_hi = lo_rank > 1.0f ? static_cast<uint32_t>(lo_rank) : 1u;
-                uint32_t hi;
-                block_select2<kPrepThreads, kSampleItems>(key, valid, rank, rank_hi, lh, lh2, sh, res, tau, hi);
-                const uint32_t range = (hi | ((1u << kShift2) - 1u)) - tau;
+                rank[2] = lo_rank > 1.0f ? static_cast<uint32_t>(lo_rank) : 1u;
+                const uint32_t mid = static_cast<uint32_t>(a + 0.5f);
+                rank[1] = mid < rank[2] ? rank[2] : (mid > rank[0] ? rank[0] : mid);
+                block_select_multi<kPrepThreads, kSampleItems, 3>(key, valid, rank, lh, sh, res, sel);
+                tau = sel[0];
+                test = sel[1];
+                const uint32_t range = (sel[2] | ((1u << kShift2) - 1u)) - tau;
                 while ((range >> binsh) > static_cast<uint32_t>(kTopBin - 1)) ++binsh;
             }
         }
     }
+    __syncthreads();
     if (threadIdx.x == 0) {
         c.state[s].tau = tau;
         c.state[s].sh = binsh;
+        c.state[s].test = test;
     }
 }
 
@@ -453,11 +477,13 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
         if (threadIdx.x == 0) c.cnt[tile] = 0;
         return;
     }
+    const uint32_t tau = c.state[gd.seg].tau, test = c.state[gd.seg].test;
+    const bool interior = t >= seg_lo && t + kWaveTile <= seg_hi;
     float a[kRows][4];
     uint32_t mask[kRows];
-    if (t >= seg_lo && t + kWaveTile <= seg_hi) {  // interior: unconditional 16-byte streaming accesses
+    if (interior) {  // unconditional 16-byte streaming accesses
         const ld_f32x4* g4 = reinterpret_cast<const ld_f32x4*>(g + t) + lane;
-        ld_f32x4* r4 = reinterpret_cast<ld_f32x4*>(r + t) + lane;
+        const ld_f32x4* r4 = reinterpret_cast<const ld_f32x4*>(r + t) + lane;
         ld_f32x4 gq[kRows], rq[kRows];
 #pragma unroll
         for (int j = 0; j < kRows; ++j) gq[j] = ld_nt_load(g4 + j * LD_WAVE);
@@ -469,7 +495,6 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
             a[j][1] = __fadd_rn(rq[j].y, gq[j].y);
             a[j][2] = __fadd_rn(rq[j].z, gq[j].z);
             a[j][3] = __fadd_rn(rq[j].w, gq[j].w);
-            ld_nt_store(ld_f32x4{a[j][0], a[j][1], a[j][2], a[j][3]}, r4 + j * LD_WAVE);
             mask[j] = 0xF;
         }
     } else {
@@ -481,21 +506,22 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
             load4(r, e0, seg_lo, seg_hi, rv);
 #pragma unroll
             for (int q = 0; q < 4; ++q) a[j][q] = __fadd_rn(rv[q], gv[q]);
-            store4(r, e0, mask[j], a[j]);
         }
     }
     // candidates, in element order (wave, row, lane, component)
-    const uint32_t tau = c.state[gd.seg].tau;
-    uint32_t flag[kRows], below[kRows], rowbase[kRows], total = 0;
+    uint32_t flag[kRows], zero[kRows], below[kRows], rowbase[kRows], total = 0;
 #pragma unroll
     for (int j = 0; j < kRows; ++j) {
         flag[j] = 0;
+        zero[j] = 0;
         rowbase[j] = total;
         below[j] = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const bool f = ((mask[j] >> q) & 1u) && ld_key(a[j][q]) >= tau;
+            const uint32_t key = ld_key(a[j][q]);
+            const bool f = ((mask[j] >> q) & 1u) && key >= tau;
             flag[j] |= static_cast<uint32_t>(f) << q;
+            zero[j] |= static_cast<uint32_t>(f && key >= test) << q;
             const uint64_t m = __ballot(f);
             below[j] += mbcnt(m);
             total += __popcll(m);
@@ -510,8 +536,20 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
         if (u < w) wbase += x;
         btot += x;
     }
-    if (threadIdx.x == 0) c.cnt[tile] = btot <= kSlot ? btot : kOverflow;
-    if (btot > kSlot || total == 0) return;
+    const bool fits = btot <= kSlot;  // else: the residual keeps r + g everywhere, the slot stays unused
+    if (threadIdx.x == 0) c.cnt[tile] = fits ? btot : kOverflow;
+    // residual: +0 where the guessed threshold selects, r + g elsewhere
+#pragma unroll
+    for (int j = 0; j < kRows; ++j) {
+        float x[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) x[q] = (fits && ((zero[j] >> q) & 1u)) ? 0.0f : a[j][q];
+        if (interior)
+            ld_nt_store(ld_f32x4{x[0], x[1], x[2], x[3]}, reinterpret_cast<ld_f32x4*>(r + t) + j * LD_WAVE + lane);
+        else
+            store4(r, t + (j * LD_WAVE + lane) * 4, mask[j], x);
+    }
+    if (!fits || total == 0) return;
     float* sv = c.cval + static_cast<int64_t>(tile) * kSlot;
     uint16_t* si = c.cidx + static_cast<int64_t>(tile) * kSlot;
 #pragma unroll
@@ -533,14 +571,15 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
 // ------------------------------------------------- passes over the candidates
 
 // A wave of a small pass owns kTilesPerWave consecutive tiles of its group. For
-// each live tile, in order: begin(tl); then item(have, val, local) for batches of
-// 64 candidates (one per lane, index order, called by all lanes together; `local`
-// is the element's offset inside the tile); then end(tl). The slots of kBatch
-// tiles are fetched together so that several loads are in flight per lane. A tile
-// whose slot overflowed is read back from the residual and filtered with the same
+// each live tile, in order: begin(u); then item(have, val, local, stored) for
+// batches of 64 candidates (one per lane, index order, called by all lanes
+// together; `local` is the element's offset inside the tile, `stored` tells that
+// the candidate comes from the slot); then end(u), u = 0.. being the tile's number
+// inside the wave. All slots of the wave are fetched before the first is used, so
+// that a wave waits for memory once. A tile whose slot overflowed is read back
+// from the residual (which then holds r + g unzeroed) and filtered with the same
 // test k_main applied.
 constexpr int kTilesPerWave = kTilesPerGroup / kWaves;
-constexpr int kBatch = 4;
 
 template <bool IDX, class Begin, class Item, class End>
 __device__ __forceinline__ void wave_tiles(const Ctx& c, const float* __restrict__ r, const GroupRange& gr,
@@ -556,116 +595,133 @@ __device__ __forceinline__ void wave_tiles(const Ctx& c, const float* __restrict
         live = nt < kTilesPerWave ? static_cast<int>(nt) : kTilesPerWave;
     }
     const uint32_t mycnt = lane < live ? c.cnt[tile0 + lane] : 0u;
-    for (int i0 = 0; i0 < live; i0 += kBatch) {
-        uint32_t cn[kBatch], x0[kBatch], x1[kBatch];
-        float v0[kBatch], v1[kBatch];
+    uint32_t x0[kTilesPerWave], x1[kTilesPerWave];
+    float v0[kTilesPerWave], v1[kTilesPerWave];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            cn[u] = (i0 + u < live) ? static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), i0 + u, LD_WAVE)) : 0u;
-            const uint32_t n = cn[u] == kOverflow ? 0u : cn[u];
-            const int64_t slot = static_cast<int64_t>(tile0 + i0 + u) * kSlot;
-            const bool h0 = static_cast<uint32_t>(lane) < n, h1 = static_cast<uint32_t>(lane + LD_WAVE) < n;
-            v0[u] = h0 ? c.cval[slot + lane] : 0.0f;
-            v1[u] = h1 ? c.cval[slot + LD_WAVE + lane] : 0.0f;
-            x0[u] = (IDX && h0) ? c.cidx[slot + lane] : 0u;
-            x1[u] = (IDX && h1) ? c.cidx[slot + LD_WAVE + lane] : 0u;
-        }
+    for (int u = 0; u < kTilesPerWave; ++u) {
+        const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
+        const uint32_t n = cn == kOverflow ? 0u : cn;
+        const int64_t slot = static_cast<int64_t>(tile0 + u) * kSlot;
+        const bool h0 = static_cast<uint32_t>(lane) < n, h1 = static_cast<uint32_t>(lane + LD_WAVE) < n;
+        v0[u] = h0 ? c.cval[slot + lane] : 0.0f;
+        v1[u] = h1 ? c.cval[slot + LD_WAVE + lane] : 0.0f;
+        x0[u] = (IDX && h0) ? c.cidx[slot + lane] : 0u;
+        x1[u] = (IDX && h1) ? c.cidx[slot + LD_WAVE + lane] : 0u;
+    }
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            if (i0 + u >= live) break;
-            const int tl = tl0 + i0 + u;
-            begin(tl);
-            if (cn[u] != kOverflow) {
-                const uint32_t n = cn[u];
-                if (n > 0) item(static_cast<uint32_t>(lane) < n, v0[u], x0[u]);
-                if (n > LD_WAVE) item(static_cast<uint32_t>(lane + LD_WAVE) < n, v1[u], x1[u]);
-                const int64_t slot = static_cast<int64_t>(tile0 + i0 + u) * kSlot;
-                for (uint32_t b0 = 2 * LD_WAVE; b0 < n; b0 += LD_WAVE) {
-                    const bool h = b0 + lane < n;
-                    const float v = h ? c.cval[slot + b0 + lane] : 0.0f;
-                    const uint32_t x = (IDX && h) ? c.cidx[slot + b0 + lane] : 0u;
-                    item(h, v, x);
-                }
-            } else {
-                const int64_t tbase = gr.base + static_cast<int64_t>(tl) * kTile;
-                for (int32_t l0 = 0; l0 < kTile; l0 += LD_WAVE) {
-                    const int64_t e = tbase + l0 + lane;
-                    const bool in = e >= gr.lo && e < gr.hi;
-                    const float v = in ? r[e] : 0.0f;
-                    item(in && ld_key(v) >= tau, v, static_cast<uint32_t>(l0 + lane));
-                }
+    for (int u = 0; u < kTilesPerWave; ++u) {
+        if (u >= live) continue;
+        const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
+        begin(u);
+        if (cn != kOverflow) {
+            if (cn > 0) item(static_cast<uint32_t>(lane) < cn, v0[u], x0[u], true);
+            if (cn > LD_WAVE) item(static_cast<uint32_t>(lane + LD_WAVE) < cn, v1[u], x1[u], true);
+            const int64_t slot = static_cast<int64_t>(tile0 + u) * kSlot;
+            for (uint32_t b0 = 2 * LD_WAVE; b0 < cn; b0 += LD_WAVE) {
+                const bool h = b0 + lane < cn;
+                const float v = h ? c.cval[slot + b0 + lane] : 0.0f;
+                const uint32_t x = (IDX && h) ? c.cidx[slot + b0 + lane] : 0u;
+                item(h, v, x, true);
             }
-            end(tl);
+        } else {
+            const int64_t tbase = tbase0 + static_cast<int64_t>(u) * kTile;
+            for (int32_t l0 = 0; l0 < kTile; l0 += LD_WAVE) {
+                const int64_t e = tbase + l0 + lane;
+                const bool in = e >= gr.lo && e < gr.hi;
+                const float v = in ? r[e] : 0.0f;
+                item(in && ld_key(v) >= tau, v, static_cast<uint32_t>(l0 + lane), false);
+            }
         }
+        end(u);
     }
 }
 
-// Fine-bin histogram of the candidates; the last workgroup of a segment finds
-// the threshold bin, or sends the segment to the full path.
+__device__ __forceinline__ void mark_full(const Ctx& c, SegState* st, const GroupRange& gr, uint32_t* list0) {
+    if (threadIdx.x == 0) {
+        st->mode = kModeFull;
+        *list0 = atomicAdd(c.fail_count, static_cast<uint32_t>(gr.ngroup));
+    }
+    __syncthreads();
+    for (int32_t q = threadIdx.x; q < gr.ngroup; q += blockDim.x) c.fail_groups[*list0 + q] = gr.group0 + q;
+}
+
+__device__ __forceinline__ GroupRange seg_range(const Ctx& c, int32_t s) {
+    GroupRange r;
+    const SegDesc d = c.desc[s];
+    const SegDesc dn = c.desc[s + 1];
+    r.seg = s;
+    r.base = align_down4(d.off);
+    r.lo = d.off;
+    r.hi = dn.off;
+    r.k = d.k;
+    r.group0 = d.group0;
+    r.ngroup = dn.group0 - d.group0;
+    r.out0 = d.out0;
+    return r;
+}
+
+// Fine-bin histogram of the candidates of one group, added to the segment's.
 __global__ __launch_bounds__(kThreads) void k_hist(const float* __restrict__ r, Ctx c) {
     __shared__ uint32_t lh[kBins];
-    __shared__ uint32_t sh[kWaves];
-    __shared__ uint32_t res[2];
-    __shared__ uint32_t list0;
     const GroupRange gr = group_range(c, blockIdx.x);
     if (gr.k == 0) return;
-    SegState* st = c.state + gr.seg;
+    const SegState* st = c.state + gr.seg;
     const uint32_t tau = st->tau, binsh = st->sh;
     for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
     __syncthreads();
     wave_tiles<false>(
         c, r, gr, blockIdx.x, tau, [](int) {},
-        [&](bool have, float v, uint32_t) {
+        [&](bool have, float v, uint32_t, bool) {
             if (have) atomicAdd(&lh[fine_bin(ld_key(v), tau, binsh)], 1u);
         },
         [](int) {});
     __syncthreads();
+    flush_hist(c.hist + static_cast<int64_t>(gr.seg) * kBins, lh);
+}
+
+// One workgroup per segment: the fine bin that holds the k-th largest key, or
+// the hand-over to the full path when the candidates are fewer than k.
+__global__ __launch_bounds__(kThreads) void k_bin(Ctx c) {
+    __shared__ uint32_t sh[kWaves];
+    __shared__ uint32_t res[2];
+    __shared__ uint32_t list0;
+    const GroupRange gr = seg_range(c, blockIdx.x);
+    if (gr.k == 0 || gr.ngroup == 0) return;
+    SegState* st = c.state + gr.seg;
     uint32_t* h = c.hist + static_cast<int64_t>(gr.seg) * kBins;
-    flush_hist(h, lh);
-    if (!last_block(&st->done[0], static_cast<uint32_t>(gr.ngroup))) return;
     if (threadIdx.x == 0) { res[0] = 0; res[1] = 0; }
     __syncthreads();
-    const uint32_t total = find_bin<kThreads, true>(h, static_cast<uint32_t>(gr.k), sh, res);
-    for (int b = threadIdx.x; b < kBins; b += kThreads) h[b] = 0;
+    const uint32_t total = find_bin<kThreads, false>(h, static_cast<uint32_t>(gr.k), sh, res);
+    for (int b = threadIdx.x; b < kBins; b += kThreads) h[b] = 0;  // the full path reuses the row
     if (total >= static_cast<uint32_t>(gr.k)) {
         if (threadIdx.x == 0) { st->prefix = res[0]; st->krem = res[1]; }
     } else {
-        // fewer than k candidates (the estimate was too high): select over the whole segment
-        if (threadIdx.x == 0) {
-            st->mode = kModeFull;
-            list0 = atomicAdd(c.fail_count, static_cast<uint32_t>(gr.ngroup));
-        }
-        __syncthreads();
-        for (int32_t q = threadIdx.x; q < gr.ngroup; q += kThreads) c.fail_groups[list0 + q] = gr.group0 + q;
+        mark_full(c, st, gr, &list0);  // the candidate threshold was too high
     }
 }
 
 // Per tile: candidates in bins above the threshold bin; the keys inside the bin
-// are gathered. The last workgroup of a segment selects the exact threshold among
-// the gathered keys, completes the per-tile counts and scans the group sums.
+// are gathered per segment.
 __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r, Ctx c) {
-    __shared__ uint32_t lh[kBins];
-    __shared__ uint32_t sh[kWaves];
-    __shared__ uint32_t res[2];
     __shared__ uint32_t wsum[kWaves];
-    __shared__ uint32_t list0;
     const GroupRange gr = group_range(c, blockIdx.x);
     SegState* st = c.state + gr.seg;
     if (gr.k == 0 || st->mode != kModeCand) return;
-    const uint32_t tau = st->tau, binsh = st->sh, b1 = st->prefix, krem1 = st->krem;
+    const uint32_t tau = st->tau, binsh = st->sh, b1 = st->prefix;
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
     uint32_t* gkey = c.gkey + static_cast<int64_t>(gr.seg) * kGatherCap;
     int32_t* gtile = c.gtile + static_cast<int64_t>(gr.seg) * kGatherCap;
-    uint32_t wave_gt = 0, gt = 0;
+    const int32_t tile0 = blockIdx.x * kTilesPerGroup + w * kTilesPerWave;
+    uint32_t wave_gt = 0, gt = 0, mine = 0;  // lane u keeps the count of the wave's tile u
     int32_t tile_of_item = 0;
     wave_tiles<false>(
         c, r, gr, blockIdx.x, tau,
-        [&](int tl) {
+        [&](int u) {
             gt = 0;
-            tile_of_item = blockIdx.x * kTilesPerGroup + tl;
+            tile_of_item = tile0 + u;
         },
-        [&](bool have, float v, uint32_t) {
+        [&](bool have, float v, uint32_t, bool) {
             const uint32_t key = ld_key(v);
             const uint32_t bin = have ? fine_bin(key, tau, binsh) : 0u;
             gt += __popcll(__ballot(have && bin > b1));
@@ -682,30 +738,39 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
                 }
             }
         },
-        [&](int tl) {
-            if (lane == 0) {
-                c.tile_gt[blockIdx.x * kTilesPerGroup + tl] = gt;
-                c.tile_eq[blockIdx.x * kTilesPerGroup + tl] = 0;
-            }
+        [&](int u) {
+            if (lane == u) mine = gt;
             wave_gt += gt;
         });
+    if (lane < kTilesPerWave) {
+        c.tile_gt[tile0 + lane] = mine;
+        c.tile_eq[tile0 + lane] = 0;
+    }
     if (lane == 0) wsum[w] = wave_gt;
     __syncthreads();
     if (threadIdx.x == 0) {
         c.group_gt[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
         c.group_eq[blockIdx.x] = 0;
     }
-    if (!last_block(&st->done[1], static_cast<uint32_t>(gr.ngroup))) return;
+}
 
-    const uint32_t ng = ld_load_coherent(&st->gcount);
+// One workgroup per segment: the exact threshold T and the number m of its ties to
+// keep, selected among the gathered keys; per-tile counts completed; group sums
+// scanned into output offsets.
+__global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
+    __shared__ uint32_t lh[kBins];
+    __shared__ uint32_t sh[kWaves];
+    __shared__ uint32_t res[2];
+    __shared__ uint32_t list0;
+    const GroupRange gr = seg_range(c, blockIdx.x);
+    SegState* st = c.state + gr.seg;
+    if (gr.k == 0 || gr.ngroup == 0 || st->mode != kModeCand) return;
+    const uint32_t krem1 = st->krem;
+    const uint32_t ng = st->gcount;
+    const uint32_t* gkey = c.gkey + static_cast<int64_t>(gr.seg) * kGatherCap;
+    const int32_t* gtile = c.gtile + static_cast<int64_t>(gr.seg) * kGatherCap;
     if (ng > static_cast<uint32_t>(kGatherCap)) {
-        // too many keys share the threshold bin (massive ties): select over the whole segment
-        if (threadIdx.x == 0) {
-            st->mode = kModeFull;
-            list0 = atomicAdd(c.fail_count, static_cast<uint32_t>(gr.ngroup));
-        }
-        __syncthreads();
-        for (int32_t q = threadIdx.x; q < gr.ngroup; q += kThreads) c.fail_groups[list0 + q] = gr.group0 + q;
+        mark_full(c, st, gr, &list0);  // too many keys share the threshold bin (massive ties)
         return;
     }
     uint32_t key[kGatherItems];
@@ -715,7 +780,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
         const uint32_t p = i * kThreads + threadIdx.x;
         key[i] = 0;
         if (p < ng) {
-            key[i] = ld_load_coherent(gkey + p);
+            key[i] = gkey[p];
             valid |= 1u << i;
         }
     }
@@ -724,8 +789,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
 #pragma unroll
     for (int i = 0; i < kGatherItems; ++i) {
         if (!((valid >> i) & 1u) || key[i] < T) continue;
-        const int32_t tile = static_cast<int32_t>(
-            ld_load_coherent(reinterpret_cast<const uint32_t*>(gtile) + i * kThreads + threadIdx.x));
+        const int32_t tile = gtile[i * kThreads + threadIdx.x];
         if (key[i] > T) {
             atomicAdd(c.tile_gt + tile, 1u);
             atomicAdd(c.group_gt + tile / kTilesPerGroup, 1u);
@@ -759,15 +823,31 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     if (threadIdx.x == 0) { st->prefix = T; st->krem = m; }
 }
 
+// Ordered emission of the records. k_main left +0 in the residual exactly where a
+// stored candidate's key reaches T_est; only where that guess and the selection
+// differ is the residual written again. A segment handed to the full path gets
+// every pre-zeroed position back instead.
 __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_t* __restrict__ out_idx,
                                                    float* __restrict__ out_val, Ctx c) {
     __shared__ uint32_t tile_out[kTilesPerGroup], tile_eqb[kTilesPerGroup];
     const GroupRange gr = group_range(c, blockIdx.x);
     const SegState* st = c.state + gr.seg;
-    if (gr.k == 0 || st->mode != kModeCand) return;
-    const uint32_t tau = st->tau, T = st->prefix, m = st->krem;
+    if (gr.k == 0) return;
+    const uint32_t tau = st->tau, test = st->test, T = st->prefix, m = st->krem;
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
+    const int tl0 = w * kTilesPerWave;
+    int64_t tbase = 0;
+    if (st->mode != kModeCand) {
+        wave_tiles<true>(
+            c, r, gr, blockIdx.x, tau,
+            [&](int u) { tbase = gr.base + static_cast<int64_t>(tl0 + u) * kTile; },
+            [&](bool have, float v, uint32_t local, bool stored) {
+                if (have && stored && ld_key(v) >= test) r[tbase + local] = v;
+            },
+            [](int) {});
+        return;
+    }
     if (w == 0) {  // offsets of the group's 64 tiles
         const int32_t tile = blockIdx.x * kTilesPerGroup + lane;
         const bool live = gr.base + static_cast<int64_t>(lane) * kTile < gr.hi;
@@ -780,27 +860,28 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     __syncthreads();
     uint32_t run_out = 0;  // records of the segment emitted before this point
     uint32_t run_eq = 0;   // ties seen before this point
-    int64_t tbase = 0;
     wave_tiles<true>(
         c, r, gr, blockIdx.x, tau,
-        [&](int tl) {
-            run_out = tile_out[tl];
-            run_eq = tile_eqb[tl];
-            tbase = gr.base + static_cast<int64_t>(tl) * kTile;
+        [&](int u) {
+            run_out = tile_out[tl0 + u];
+            run_eq = tile_eqb[tl0 + u];
+            tbase = gr.base + static_cast<int64_t>(tl0 + u) * kTile;
         },
-        [&](bool have, float v, uint32_t local) {
+        [&](bool have, float v, uint32_t local, bool stored) {
             const uint32_t key = ld_key(v);
             const bool is_gt = have && key > T;
             const bool is_eq = have && key == T;
             const uint64_t mg = __ballot(is_gt), me = __ballot(is_eq);
             const uint32_t eq_rank = run_eq + mbcnt(me);
-            if (is_gt || (is_eq && eq_rank < m)) {
+            const bool selected = is_gt || (is_eq && eq_rank < m);
+            const int64_t e = tbase + local;
+            if (selected) {
                 const int64_t pos = gr.out0 + run_out + mbcnt(mg) + (umin(eq_rank, m) - umin(run_eq, m));
-                const int64_t e = tbase + local;
                 out_idx[pos] = static_cast<int32_t>(e);
                 out_val[pos] = v;
-                r[e] = 0.0f;
             }
+            const bool zeroed = stored && key >= test;
+            if (have && selected != zeroed) r[e] = selected ? 0.0f : v;
             const uint32_t eq_end = run_eq + __popcll(me);
             run_out += __popcll(mg) + (umin(eq_end, m) - umin(run_eq, m));
             run_eq = eq_end;
@@ -1075,35 +1156,39 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
         int64_t out0 = 0;
         int32_t group0 = 0;
         for (int32_t s0 = 0; s0 < n_seg; s0 += kSegPerLaunch) {
-            PrepBatch pb;
+            UploadBatch ub;
             const int32_t cnt = (n_seg - s0) < kSegPerLaunch ? (n_seg - s0) : kSegPerLaunch;
-            pb.out0 = out0;
-            pb.group0 = group0;
-            pb.first = s0;
-            pb.count = cnt;
-            pb.n_seg = n_seg;
-            pb.no_estimate = (strategy == LD_COMPRESS_FULL);
+            ub.out0 = out0;
+            ub.group0 = group0;
+            ub.first = s0;
+            ub.count = cnt;
+            ub.n_seg = n_seg;
             for (int32_t j = 0; j <= kSegPerLaunch; ++j) {
                 const int32_t q = (s0 + j <= n_seg) ? (s0 + j) : n_seg;
-                pb.off[j] = static_cast<int32_t>(seg_off[q]);
-                if (j < kSegPerLaunch) pb.k[j] = (s0 + j < n_seg) ? seg_k[s0 + j] : 0;
+                ub.off[j] = static_cast<int32_t>(seg_off[q]);
+                if (j < kSegPerLaunch) ub.k[j] = (s0 + j < n_seg) ? seg_k[s0 + j] : 0;
             }
             for (int32_t j = 0; j < cnt; ++j) {
                 out0 += seg_k[s0 + j];
                 group0 += groups_of(seg_off[s0 + j], seg_off[s0 + j + 1]);
             }
-            k_prep<<<dim3(cnt), dim3(kPrepThreads), 0, st>>>(grad, residual, pb, c);
+            k_upload<<<dim3(1), dim3(512), 0, st>>>(ub, c);
             if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
         }
     }
-    if (n_group == 0) return LD_OK;
     const dim3 block(kThreads);
+    const dim3 sgrid(static_cast<uint32_t>(n_seg));
+    k_prep<<<sgrid, dim3(kPrepThreads), 0, st>>>(grad, residual, c, strategy == LD_COMPRESS_FULL ? 1 : 0);
+    if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
+    if (n_group == 0) return LD_OK;
     const dim3 grid(static_cast<uint32_t>(n_group));
     k_main<<<dim3(static_cast<uint32_t>(n_group * kTilesPerGroup)), block, 0, st>>>(grad, residual, c);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (K == 0) return LD_OK;
     k_hist<<<grid, block, 0, st>>>(residual, c);
+    k_bin<<<sgrid, block, 0, st>>>(c);
     k_gather<<<grid, block, 0, st>>>(residual, c);
+    k_select<<<sgrid, block, 0, st>>>(c);
     k_emit<<<grid, block, 0, st>>>(residual, out_idx, out_val, c);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     // segments handed to the full path (normally none: these exit at once)
