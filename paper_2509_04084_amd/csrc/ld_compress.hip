@@ -61,10 +61,16 @@ constexpr int kBins = 2048;
 constexpr int kTopBin = kBins - 1;
 constexpr int kShift1 = 20, kShift2 = 9;          // radix digits: [30:20] [19:9] [8:0]
 constexpr int kPrepThreads = 1024;
-constexpr int kSampleItems = 16;
+#ifndef LD_SAMPLE_ITEMS
+#define LD_SAMPLE_ITEMS 16
+#endif
+#ifndef LD_SAMPLE_Z
+#define LD_SAMPLE_Z 6.5f
+#endif
+constexpr int kSampleItems = LD_SAMPLE_ITEMS;
 constexpr int kSample = kPrepThreads * kSampleItems;  // 16384 sampled elements per segment
 constexpr int kSampleRuns = kSample / LD_WAVE;        // as 256 runs of 64 consecutive elements
-constexpr float kSampleZ = 6.5f;                  // safety margin of the rank estimate, in sigmas
+constexpr float kSampleZ = LD_SAMPLE_Z;                  // safety margin of the rank estimate, in sigmas
 constexpr int kGatherCap = 4096;                  // keys of the threshold bin, per segment
 constexpr int kGatherItems = kGatherCap / kThreads;
 constexpr int kSegPerLaunch = 448;
@@ -362,19 +368,20 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x) {
 
 // Segment tables of one batch: prefix sums over the batch entries before each one.
 __global__ __launch_bounds__(512) void k_upload(UploadBatch ub, Ctx c) {
+    __shared__ uint32_t sh[512 / LD_WAVE];
     const int j = threadIdx.x;
-    if (j >= ub.count) return;
-    int64_t ks = 0;
-    int32_t groups = 0;
-    for (int i = 0; i < j; ++i) {
-        groups += groups_of(ub.off[i], ub.off[i + 1]);
-        ks += ub.k[i];
-    }
+    const bool live = j < ub.count;
+    const uint32_t my_groups = live ? static_cast<uint32_t>(groups_of(ub.off[j], ub.off[j + 1])) : 0u;
+    const uint32_t my_k = live ? static_cast<uint32_t>(ub.k[j]) : 0u;  // the batch's sum is below 2^31
+    uint32_t total;
+    const uint32_t groups = block_escan<512>(my_groups, sh, total);
+    const uint32_t ks = block_escan<512>(my_k, sh, total);
+    if (!live) return;
     const int s = ub.first + j;
-    c.desc[s] = SegDesc{ub.off[j], ub.out0 + ks, ub.k[j], ub.group0 + groups};
+    c.desc[s] = SegDesc{ub.off[j], ub.out0 + ks, ub.k[j], ub.group0 + static_cast<int32_t>(groups)};
     if (s == ub.n_seg - 1)
-        c.desc[s + 1] = SegDesc{ub.off[j + 1], ub.out0 + ks + ub.k[j], 0,
-                                ub.group0 + groups + groups_of(ub.off[j], ub.off[j + 1])};
+        c.desc[s + 1] = SegDesc{ub.off[j + 1], ub.out0 + ks + my_k, 0,
+                                ub.group0 + static_cast<int32_t>(groups + my_groups)};
     if (s == 0) *c.fail_count = 0;
 }
 
