@@ -6,22 +6,34 @@
 // p = fl32(lr*val); w[idx] = fl32(w[idx] - p).
 //
 // Two strategies with identical results:
-//  * sweep   - one streaming pass over w.  A wave owns a 4096-element sub-tile
-//              held in LDS, pulls the records of every diff that fall into it
-//              (ranges precomputed by a binary-search kernel) and applies them
-//              diff after diff.  LDS operations of one wave execute in issue
-//              order, so the cross-diff order on an element needs no barrier.
-//              HBM traffic: 8n + 8*sum(K) bytes + the range table.
+//  * sweep   - one streaming pass over w.  A wave owns an 8192-element sub-tile
+//              held in LDS, pulls the records of every diff that fall into it and
+//              applies them diff after diff.  LDS operations of one wave execute
+//              in issue order, so the cross-diff order on an element needs no
+//              barrier.  Where a diff's records for the sub-tile start is not
+//              looked up in a table: a small kernel finds the record range of
+//              every chunk of 16 sub-tiles by binary search, the wave
+//              interpolates inside its chunk, loads a 128-record window a little
+//              before the guess and keeps the records that fall into its
+//              sub-tile.  The guess is checked (the window must begin before the
+//              sub-tile does, and end after it); a miss costs a binary search
+//              inside the chunk or one more window, never a wrong result.
+//              HBM traffic: 8n + 8*sum(K) bytes + the chunk table.
 //  * scatter - one kernel per diff, one thread per record; for windows that
 //              touch only a small part of w.
+#include <limits.h>
+
 #include "ld_common.h"
 
 namespace {
 
-constexpr int kSub = 4096;     // elements per wave sub-tile (16 KB of LDS)
-constexpr int kWaves = 4;      // waves per block
-constexpr int kGroupMax = 128; // diffs per launch (pointer table travels as a kernel argument)
-constexpr int kPrefetch = 8;   // diffs whose records are loaded before any is applied
+constexpr int kSub = 8192;                 // elements per wave sub-tile (32 KB of LDS, 5 waves per CU)
+constexpr int kChunkSubs = 16;             // sub-tiles per chunk of the range table
+constexpr int64_t kChunk = static_cast<int64_t>(kSub) * kChunkSubs;
+constexpr int kGroupMax = 64;              // diffs per launch (pointer table travels as a kernel argument)
+constexpr int kWin = 2;                    // 64-record windows per diff loaded ahead
+constexpr int kPre = 10;                   // diffs whose windows are loaded before any is applied
+constexpr int kMargin = 40;                // records the window starts before the interpolated position
 
 struct DiffTable {
     const int32_t* idx[kGroupMax];
@@ -38,12 +50,11 @@ __device__ __forceinline__ int32_t lower_bound_idx(const int32_t* __restrict__ i
     return lo;
 }
 
-// tab[t*(nsub+1) + b] = number of records of diff t with idx < min(n, b*kSub).
+// ctab[t*(nchunk+1) + b] = number of records of diff t with idx < min(n, b*kChunk).
 // A workgroup covers 256 consecutive boundaries of one diff: two threads bracket
-// the whole run with full searches, then every thread bisects inside the bracket
-// (a few KB of indices that the workgroup shares through the cache).
-__global__ __launch_bounds__(256) void k_partition(DiffTable tb, int64_t n, int32_t nsub,
-                                                   int32_t* __restrict__ tab) {
+// the whole run with full searches, then every thread bisects inside the bracket.
+__global__ __launch_bounds__(256) void k_chunks(DiffTable tb, int64_t n, int32_t nchunk,
+                                                int32_t* __restrict__ ctab) {
     __shared__ int32_t bracket[2];
     const int32_t b0 = blockIdx.x * 256;
     const int32_t b = b0 + threadIdx.x;
@@ -52,16 +63,16 @@ __global__ __launch_bounds__(256) void k_partition(DiffTable tb, int64_t n, int3
     const int32_t K = tb.K[t];
     if (threadIdx.x < 2) {
         int32_t bb = threadIdx.x == 0 ? b0 : b0 + 255;
-        if (bb > nsub) bb = nsub;
-        int64_t target = static_cast<int64_t>(bb) * kSub;
+        if (bb > nchunk) bb = nchunk;
+        int64_t target = static_cast<int64_t>(bb) * kChunk;
         if (target > n) target = n;
         bracket[threadIdx.x] = lower_bound_idx(idx, 0, K, target);
     }
     __syncthreads();
-    if (b > nsub) return;
-    int64_t target = static_cast<int64_t>(b) * kSub;
+    if (b > nchunk) return;
+    int64_t target = static_cast<int64_t>(b) * kChunk;
     if (target > n) target = n;
-    tab[static_cast<int64_t>(t) * (nsub + 1) + b] = lower_bound_idx(idx, bracket[0], bracket[1], target);
+    ctab[static_cast<int64_t>(t) * (nchunk + 1) + b] = lower_bound_idx(idx, bracket[0], bracket[1], target);
 }
 
 __device__ __forceinline__ void apply_record(float* tile, int32_t local, float val, float lr) {
@@ -69,75 +80,114 @@ __device__ __forceinline__ void apply_record(float* tile, int32_t local, float v
     tile[local] = __fsub_rn(tile[local], p);
 }
 
-__global__ __launch_bounds__(256) void k_merge_sweep(float* __restrict__ w, int64_t n, int32_t nsub,
-                                                     DiffTable tb, int32_t W,
-                                                     const int32_t* __restrict__ tab, float lr) {
-    __shared__ float tile_all[kWaves][kSub];
-    const int wv = threadIdx.x >> 6;
-    const int lane = threadIdx.x & 63;
-    const int64_t sub = static_cast<int64_t>(blockIdx.x) * kWaves + wv;
-    if (sub >= nsub) return;  // waves are independent: no block barrier anywhere below
-    float* tile = tile_all[wv];
-    const int64_t lo = sub * kSub;
-    const int32_t len = static_cast<int32_t>((n - lo) < kSub ? (n - lo) : kSub);
+// Applies the records of one diff at positions [p, end) that fall below hi (all of
+// them are at or above the sub-tile's first element), 64 at a time.
+__device__ __forceinline__ void apply_from(float* tile, const int32_t* __restrict__ idx,
+                                           const float* __restrict__ val, int32_t p, int32_t end,
+                                           int32_t lo, int32_t hi, float lr, int lane) {
+    for (; p < end; p += LD_WAVE) {
+        const bool have = p + lane < end;
+        const int32_t i = have ? idx[p + lane] : INT_MAX;
+        const float v = have ? val[p + lane] : 0.0f;
+        if (i < hi) apply_record(tile, i - lo, v, lr);
+        if (__ballot(i >= hi)) break;
+    }
+}
+
+__global__ __launch_bounds__(LD_WAVE) void k_merge_sweep(float* __restrict__ w, int64_t n, int32_t nchunk,
+                                                         DiffTable tb, int32_t W,
+                                                         const int32_t* __restrict__ ctab, float lr) {
+    __shared__ float tile[kSub];
+    const int lane = threadIdx.x;
+    // consecutive workgroups go to different XCDs (each with an L2 of its own): give every XCD one
+    // contiguous eighth of w, so that the overlapping record windows of neighbouring sub-tiles hit its L2
+    const int64_t per = (static_cast<int64_t>(gridDim.x) + 7) / 8;
+    const int64_t sub = static_cast<int64_t>(blockIdx.x % 8) * per + blockIdx.x / 8;
+    if (sub * kSub >= n) return;
+    const int64_t lo64 = sub * kSub;
+    const int32_t len = static_cast<int32_t>((n - lo64) < kSub ? (n - lo64) : kSub);
+    const int32_t lo = static_cast<int32_t>(lo64), hi = lo + len;  // n <= INT_MAX
     const bool full = (len == kSub);
 
+    ld_f32x4 x[kSub / 4 / LD_WAVE];
     if (full) {
-        const ld_f32x4* src = reinterpret_cast<const ld_f32x4*>(w + lo);
+        const ld_f32x4* src = reinterpret_cast<const ld_f32x4*>(w + lo64);
 #pragma unroll
-        for (int j = 0; j < kSub / 4 / LD_WAVE; ++j) {
-            const ld_f32x4 x = ld_nt_load(src + j * LD_WAVE + lane);
-            reinterpret_cast<ld_f32x4*>(tile)[j * LD_WAVE + lane] = x;
-        }
-    } else {
-        for (int32_t e = lane; e < len; e += LD_WAVE) tile[e] = w[lo + e];
+        for (int j = 0; j < kSub / 4 / LD_WAVE; ++j) x[j] = ld_nt_load(src + j * LD_WAVE + lane);
     }
 
-    const int64_t stride = static_cast<int64_t>(nsub) + 1;
-    const int32_t base = static_cast<int32_t>(lo);
-    for (int32_t t0 = 0; t0 < W; t0 += kPrefetch) {
-        int32_t p0[kPrefetch], cnt[kPrefetch], ri[kPrefetch];
-        float rv[kPrefetch];
+    // lane t: where diff t's records of this chunk lie, and the guess for this sub-tile
+    const int32_t chunk = static_cast<int32_t>(sub / kChunkSubs), part = static_cast<int32_t>(sub % kChunkSubs);
+    int32_t c0 = 0, c1 = 0;
+    if (lane < W) {
+        const int32_t* row = ctab + static_cast<int64_t>(lane) * (nchunk + 1) + chunk;
+        c0 = row[0];
+        c1 = row[1];
+    }
+    int32_t start = c0 + ((c1 - c0) * part) / kChunkSubs - kMargin;
+    if (start < c0) start = c0;
+
+    if (full) {
 #pragma unroll
-        for (int g = 0; g < kPrefetch; ++g) {
-            const int32_t t = t0 + g;
-            if (t < W) {
-                p0[g] = tab[t * stride + sub];
-                cnt[g] = tab[t * stride + sub + 1] - p0[g];
-            } else {
-                p0[g] = 0;
-                cnt[g] = 0;
+        for (int j = 0; j < kSub / 4 / LD_WAVE; ++j) reinterpret_cast<ld_f32x4*>(tile)[j * LD_WAVE + lane] = x[j];
+    } else {
+        for (int32_t e = lane; e < len; e += LD_WAVE) tile[e] = w[lo64 + e];
+    }
+    __syncthreads();  // one wave: only orders the vector fill before the scalar updates
+
+    for (int32_t t0 = 0; t0 < W; t0 += kPre) {
+        int32_t s_[kPre], e_[kPre], b_[kPre], ri[kPre][kWin];
+        float rv[kPre][kWin];
+#pragma unroll
+        for (int g = 0; g < kPre; ++g) {
+            const int t = (t0 + g < W) ? t0 + g : 0;
+            s_[g] = __builtin_amdgcn_readlane(start, t);
+            b_[g] = __builtin_amdgcn_readlane(c0, t);
+            e_[g] = (t0 + g < W) ? __builtin_amdgcn_readlane(c1, t) : s_[g];  // past W: an empty window
+            const int32_t* __restrict__ ip = tb.idx[t];
+            const float* __restrict__ vp = tb.val[t];
+#pragma unroll
+            for (int u = 0; u < kWin; ++u) {
+                const int32_t p = s_[g] + u * LD_WAVE + lane;
+                const bool h = p < e_[g];
+                ri[g][u] = h ? ip[p] : INT_MAX;
+                rv[g][u] = h ? vp[p] : 0.0f;
             }
         }
 #pragma unroll
-        for (int g = 0; g < kPrefetch; ++g) {
-            ri[g] = 0;
-            rv[g] = 0.0f;
-            if (lane < cnt[g]) {
-                ri[g] = __builtin_nontemporal_load(tb.idx[t0 + g] + p0[g] + lane);
-                rv[g] = __builtin_nontemporal_load(tb.val[t0 + g] + p0[g] + lane);
-            }
-        }
+        for (int g = 0; g < kPre; ++g) {
+            if (s_[g] < e_[g]) {
+                const int t = t0 + g;
+                const int32_t first = __builtin_amdgcn_readfirstlane(ri[g][0]);
+                if (s_[g] == b_[g] || first <= lo) {
+                    // the window begins before the sub-tile's records do
+                    bool more = true;
 #pragma unroll
-        for (int g = 0; g < kPrefetch; ++g) {
-            if (lane < cnt[g]) apply_record(tile, ri[g] - base, rv[g], lr);
-            // more than 64 records of this diff in the sub-tile (density > 1.5 %)
-            for (int32_t j = lane + LD_WAVE; j < cnt[g]; j += LD_WAVE) {
-                const int32_t i = tb.idx[t0 + g][p0[g] + j];
-                const float v = tb.val[t0 + g][p0[g] + j];
-                apply_record(tile, i - base, v, lr);
+                    for (int u = 0; u < kWin; ++u) {
+                        if (more) {
+                            if (ri[g][u] >= lo && ri[g][u] < hi) apply_record(tile, ri[g][u] - lo, rv[g][u], lr);
+                            more = !__ballot(ri[g][u] >= hi);
+                        }
+                    }
+                    if (more) apply_from(tile, tb.idx[t], tb.val[t], s_[g] + kWin * LD_WAVE, e_[g], lo, hi, lr, lane);
+                } else {
+                    // guess too late: find the first record of the sub-tile inside the chunk
+                    const int32_t p = lower_bound_idx(tb.idx[t], b_[g], s_[g], lo);
+                    apply_from(tile, tb.idx[t], tb.val[t], p, e_[g], lo, hi, lr, lane);
+                }
             }
             __builtin_amdgcn_wave_barrier();  // keep diff g's LDS traffic ahead of diff g+1's
         }
     }
 
+    __syncthreads();
     if (full) {
-        ld_f32x4* dst = reinterpret_cast<ld_f32x4*>(w + lo);
+        ld_f32x4* dst = reinterpret_cast<ld_f32x4*>(w + lo64);
 #pragma unroll
         for (int j = 0; j < kSub / 4 / LD_WAVE; ++j)
             ld_nt_store(reinterpret_cast<const ld_f32x4*>(tile)[j * LD_WAVE + lane], dst + j * LD_WAVE + lane);
     } else {
-        for (int32_t e = lane; e < len; e += LD_WAVE) w[lo + e] = tile[e];
+        for (int32_t e = lane; e < len; e += LD_WAVE) w[lo64 + e] = tile[e];
     }
 }
 
@@ -153,6 +203,7 @@ __global__ __launch_bounds__(256) void k_merge_scatter(float* __restrict__ w,
 }
 
 int32_t sub_tiles(int64_t n) { return static_cast<int32_t>((n + kSub - 1) / kSub); }
+int32_t chunks(int64_t n) { return static_cast<int32_t>((n + kChunk - 1) / kChunk); }
 
 ld_status check_args(float* w, int64_t n, const int32_t* const* idx, const float* const* val,
                      const int64_t* K, int32_t W) {
@@ -175,7 +226,7 @@ extern "C" size_t ld_merge_sparse_workspace(int64_t n, int32_t W, const int64_t*
     (void)K;
     if (n <= 0 || W <= 0) return 256;
     const int64_t group = W < kGroupMax ? W : kGroupMax;
-    return ld_round_up(static_cast<size_t>(group) * (static_cast<size_t>(sub_tiles(n)) + 1) * 4, 256);
+    return ld_round_up(static_cast<size_t>(group) * (static_cast<size_t>(chunks(n)) + 1) * 4, 256);
 }
 
 extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t* const* idx,
@@ -207,8 +258,8 @@ extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t
     if (!workspace || !ld_aligned(workspace, 256) ||
         workspace_bytes < ld_merge_sparse_workspace(n, W, K))
         return LD_ERR_WORKSPACE;
-    const int32_t nsub = sub_tiles(n);
-    int32_t* tab = static_cast<int32_t*>(workspace);
+    const int32_t nsub = sub_tiles(n), nchunk = chunks(n);
+    int32_t* ctab = static_cast<int32_t*>(workspace);
     for (int32_t g0 = 0; g0 < W; g0 += kGroupMax) {
         const int32_t gw = (W - g0) < kGroupMax ? (W - g0) : kGroupMax;
         DiffTable tb;
@@ -218,10 +269,9 @@ extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t
             tb.val[t] = live ? val[g0 + t] : nullptr;
             tb.K[t] = live ? static_cast<int32_t>(K[g0 + t]) : 0;
         }
-        k_partition<<<dim3((nsub + 1 + 255) / 256, gw), dim3(256), 0, s>>>(tb, n, nsub, tab);
+        k_chunks<<<dim3((nchunk + 1 + 255) / 256, gw), dim3(256), 0, s>>>(tb, n, nchunk, ctab);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
-        k_merge_sweep<<<dim3((nsub + kWaves - 1) / kWaves), dim3(256), 0, s>>>(w, n, nsub, tb, gw,
-                                                                                tab, lr);
+        k_merge_sweep<<<dim3((nsub + 7) / 8 * 8), dim3(LD_WAVE), 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     }
     return LD_OK;
