@@ -51,9 +51,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / LD_WAVE;
-constexpr int kRows = 4;                          // float4 rows per lane
-constexpr int kWaveTile = LD_WAVE * 4 * kRows;    // 1024 consecutive elements per wave
-constexpr int kTile = kWaves * kWaveTile;         // 4096 elements per k_main workgroup
+constexpr int kTile = 4096;                       // elements per k_main workgroup
 constexpr int kSlot = 256;                        // candidate slots per tile (6.25 %)
 constexpr int kTilesPerGroup = 64;
 constexpr int kGroup = kTile * kTilesPerGroup;    // 262144 elements per small-pass workgroup
@@ -76,6 +74,7 @@ constexpr int kGatherItems = kGatherCap / kThreads;
 constexpr int kSegPerLaunch = 448;
 constexpr int kFullGrid = 1024;                   // workgroups of the (normally idle) k_full_* kernels
 constexpr uint32_t kModeCand = 0, kModeFull = 1;
+
 constexpr uint32_t kOverflow = 0xFFFFFFFFu;       // tile count: slot too small, read the residual
 
 struct SegDesc {        // one per segment plus a sentinel
@@ -471,33 +470,38 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
 
 // -------------------------------------------------------------------- k_main
 
-__global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, float* __restrict__ r, Ctx c) {
-    __shared__ uint32_t wtot[kWaves];
-    const int32_t tile = blockIdx.x;
+constexpr int kMainWaves = 1;                                // waves per tile
+constexpr int kMainRows = kTile / (kMainWaves * LD_WAVE * 4);  // float4 rows per lane
+constexpr int kMainWaveTile = LD_WAVE * 4 * kMainRows;      // consecutive elements per wave
+
+__global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __restrict__ g, float* __restrict__ r, Ctx c) {
+    __shared__ uint32_t wtot[kMainWaves];
+    // consecutive workgroups go to different XCDs: each XCD streams one contiguous eighth of the tiles
+    const int32_t tile = static_cast<int32_t>((blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8);
     const GroupDesc gd = c.gdesc[tile / kTilesPerGroup];
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
     const int64_t tbase = gd.base + static_cast<int64_t>(tile % kTilesPerGroup) * kTile;
-    const int64_t t = tbase + w * kWaveTile;
+    const int64_t t = tbase + w * kMainWaveTile;
     const int64_t seg_lo = c.desc[gd.seg].off, seg_hi = c.desc[gd.seg + 1].off;
     if (tbase >= seg_hi) {  // tile slot past the end of the segment
         if (threadIdx.x == 0) c.cnt[tile] = 0;
         return;
     }
     const uint32_t tau = c.state[gd.seg].tau, test = c.state[gd.seg].test;
-    const bool interior = t >= seg_lo && t + kWaveTile <= seg_hi;
-    float a[kRows][4];
-    uint32_t mask[kRows];
+    const bool interior = t >= seg_lo && t + kMainWaveTile <= seg_hi;
+    float a[kMainRows][4];
+    uint32_t mask[kMainRows];
     if (interior) {  // unconditional 16-byte streaming accesses
         const ld_f32x4* g4 = reinterpret_cast<const ld_f32x4*>(g + t) + lane;
         const ld_f32x4* r4 = reinterpret_cast<const ld_f32x4*>(r + t) + lane;
-        ld_f32x4 gq[kRows], rq[kRows];
+        ld_f32x4 gq[kMainRows], rq[kMainRows];
 #pragma unroll
-        for (int j = 0; j < kRows; ++j) gq[j] = ld_nt_load(g4 + j * LD_WAVE);
+        for (int j = 0; j < kMainRows; ++j) gq[j] = ld_nt_load(g4 + j * LD_WAVE);
 #pragma unroll
-        for (int j = 0; j < kRows; ++j) rq[j] = ld_nt_load(r4 + j * LD_WAVE);
+        for (int j = 0; j < kMainRows; ++j) rq[j] = ld_nt_load(r4 + j * LD_WAVE);
 #pragma unroll
-        for (int j = 0; j < kRows; ++j) {
+        for (int j = 0; j < kMainRows; ++j) {
             a[j][0] = __fadd_rn(rq[j].x, gq[j].x);
             a[j][1] = __fadd_rn(rq[j].y, gq[j].y);
             a[j][2] = __fadd_rn(rq[j].z, gq[j].z);
@@ -506,7 +510,7 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
         }
     } else {
 #pragma unroll
-        for (int j = 0; j < kRows; ++j) {
+        for (int j = 0; j < kMainRows; ++j) {
             const int64_t e0 = t + (j * LD_WAVE + lane) * 4;
             float gv[4], rv[4];
             mask[j] = load4(g, e0, seg_lo, seg_hi, gv);
@@ -516,13 +520,12 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
         }
     }
     // candidates, in element order (wave, row, lane, component)
-    uint32_t flag[kRows], zero[kRows], below[kRows], rowbase[kRows], total = 0;
+    uint32_t flag[kMainRows], zero[kMainRows], pos0[kMainRows], total = 0;
 #pragma unroll
-    for (int j = 0; j < kRows; ++j) {
+    for (int j = 0; j < kMainRows; ++j) {
         flag[j] = 0;
         zero[j] = 0;
-        rowbase[j] = total;
-        below[j] = 0;
+        pos0[j] = total;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const uint32_t key = ld_key(a[j][q]);
@@ -530,24 +533,27 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
             flag[j] |= static_cast<uint32_t>(f) << q;
             zero[j] |= static_cast<uint32_t>(f && key >= test) << q;
             const uint64_t m = __ballot(f);
-            below[j] += mbcnt(m);
+            pos0[j] += mbcnt(m);
             total += __popcll(m);
         }
     }
-    if (lane == 0) wtot[w] = total;
-    __syncthreads();
-    uint32_t wbase = 0, btot = 0;
+    uint32_t wbase = 0, btot = total;
+    if (kMainWaves > 1) {
+        if (lane == 0) wtot[w] = total;
+        __syncthreads();
+        btot = 0;
 #pragma unroll
-    for (int u = 0; u < kWaves; ++u) {
-        const uint32_t x = wtot[u];
-        if (u < w) wbase += x;
-        btot += x;
+        for (int u = 0; u < kMainWaves; ++u) {
+            const uint32_t x = wtot[u];
+            if (u < w) wbase += x;
+            btot += x;
+        }
     }
     const bool fits = btot <= kSlot;  // else: the residual keeps r + g everywhere, the slot stays unused
     if (threadIdx.x == 0) c.cnt[tile] = fits ? btot : kOverflow;
     // residual: +0 where the guessed threshold selects, r + g elsewhere
 #pragma unroll
-    for (int j = 0; j < kRows; ++j) {
+    for (int j = 0; j < kMainRows; ++j) {
         float x[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) x[q] = (fits && ((zero[j] >> q) & 1u)) ? 0.0f : a[j][q];
@@ -560,10 +566,10 @@ __global__ __launch_bounds__(kThreads) void k_main(const float* __restrict__ g, 
     float* sv = c.cval + static_cast<int64_t>(tile) * kSlot;
     uint16_t* si = c.cidx + static_cast<int64_t>(tile) * kSlot;
 #pragma unroll
-    for (int j = 0; j < kRows; ++j) {
+    for (int j = 0; j < kMainRows; ++j) {
         if (flag[j] == 0) continue;
-        uint32_t pos = wbase + rowbase[j] + below[j];
-        const uint32_t local = w * kWaveTile + (j * LD_WAVE + lane) * 4;
+        uint32_t pos = wbase + pos0[j];
+        const uint32_t local = w * kMainWaveTile + (j * LD_WAVE + lane) * 4;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             if ((flag[j] >> q) & 1u) {
@@ -1189,7 +1195,7 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (n_group == 0) return LD_OK;
     const dim3 grid(static_cast<uint32_t>(n_group));
-    k_main<<<dim3(static_cast<uint32_t>(n_group * kTilesPerGroup)), block, 0, st>>>(grad, residual, c);
+    k_main<<<dim3(static_cast<uint32_t>(n_group * kTilesPerGroup)), dim3(kMainWaves * LD_WAVE), 0, st>>>(grad, residual, c);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (K == 0) return LD_OK;
     k_hist<<<grid, block, 0, st>>>(residual, c);

@@ -59,7 +59,10 @@ __device__ __forceinline__ void copy_block(const unsigned char* __restrict__ src
 __global__ __launch_bounds__(kCopyThreads) void k_snapshot(const unsigned char* __restrict__ src,
                                                            unsigned char* __restrict__ dst,
                                                            int64_t bytes) {
-    copy_block(src, dst, bytes, blockIdx.x);
+    // consecutive workgroups go to different XCDs: each XCD copies one contiguous eighth
+    const int64_t per = (static_cast<int64_t>(gridDim.x) + 7) / 8;
+    const int64_t blk = static_cast<int64_t>(blockIdx.x % 8) * per + blockIdx.x / 8;
+    if (blk * kCopyBlockBytes < bytes) copy_block(src, dst, bytes, blk);
 }
 
 __global__ __launch_bounds__(kCopyThreads) void k_snapshot_batch(CopyBatch cb) {
@@ -98,58 +101,69 @@ __device__ __forceinline__ void adam_step(float& w, float& m, float& v, float g,
 }
 
 constexpr int kAdamThreads = 256;
-constexpr int kAdamVec = 8;                                // elements per thread: one 16-byte bf16 load per step
-constexpr int kAdamBlockElems = kAdamThreads * kAdamVec;   // 2048 elements per workgroup
+constexpr int kAdamH = 4;                          // 16-byte fp32 vectors per thread and array
+constexpr int kAdamBlockElems = kAdamThreads * 4 * kAdamH; // elements per workgroup
 
-// Replays steps [t0, t0 + WT) of the window (those below a.W) on 8 consecutive
-// elements per thread. One workgroup per 2048 elements, in address order; all
-// gradient loads of the WT steps are issued before the first is used.
+typedef uint32_t ld_u32x2 __attribute__((ext_vector_type(2)));
+
+// Replays steps [t0, t0 + WT) of the window (those below a.W). One workgroup per
+// kAdamBlockElems consecutive elements; every load instruction of a wave covers
+// one contiguous run (16 bytes of fp32 state or 8 bytes of bf16 gradient per
+// lane), and all loads are issued before the first value is used. Consecutive
+// workgroups go to different XCDs, so each XCD is given one contiguous eighth of
+// the arrays (its address translations and DRAM pages stay its own).
 template <int WT>
 __global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, float* __restrict__ m,
                                                        float* __restrict__ v, int64_t n, AdamArgs a, int t0) {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * kAdamThreads + threadIdx.x;  // 8-element vector index
-    const int64_t e0 = i * kAdamVec;
-    if (e0 + kAdamVec <= n) {
-        ld_f32x4 wv[2], mv[2], vv[2];
-        ld_u32x4 gq[WT];
-        ld_f32x4* w4 = reinterpret_cast<ld_f32x4*>(w) + i * 2;
-        ld_f32x4* m4 = reinterpret_cast<ld_f32x4*>(m) + i * 2;
-        ld_f32x4* v4 = reinterpret_cast<ld_f32x4*>(v) + i * 2;
+    const int64_t per = (static_cast<int64_t>(gridDim.x) + 7) / 8;
+    const int64_t blk = static_cast<int64_t>(blockIdx.x % 8) * per + blockIdx.x / 8;
+    const int64_t b0 = blk * kAdamBlockElems;
+    if (b0 >= n) return;
+    if (b0 + kAdamBlockElems <= n) {
+        const int64_t q0 = b0 / 4 + threadIdx.x;  // index of the thread's first 4-element vector
+        ld_f32x4 wv[kAdamH], mv[kAdamH], vv[kAdamH];
+        ld_u32x2 gq[WT][kAdamH];
 #pragma unroll
         for (int t = 0; t < WT; ++t)
-            gq[t] = (t0 + t < a.W) ? ld_nt_load(reinterpret_cast<const ld_u32x4*>(a.grad[t0 + t]) + i)
-                                   : ld_u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            wv[h] = ld_nt_load(w4 + h);
-            mv[h] = ld_nt_load(m4 + h);
-            vv[h] = ld_nt_load(v4 + h);
+            for (int h = 0; h < kAdamH; ++h)
+                gq[t][h] = (t0 + t < a.W) ? __builtin_nontemporal_load(reinterpret_cast<const ld_u32x2*>(a.grad[t0 + t]) +
+                                                                       q0 + h * kAdamThreads)
+                                          : ld_u32x2{0u, 0u};
+        ld_f32x4* w4 = reinterpret_cast<ld_f32x4*>(w) + q0;
+        ld_f32x4* m4 = reinterpret_cast<ld_f32x4*>(m) + q0;
+        ld_f32x4* v4 = reinterpret_cast<ld_f32x4*>(v) + q0;
+#pragma unroll
+        for (int h = 0; h < kAdamH; ++h) {
+            wv[h] = ld_nt_load(w4 + h * kAdamThreads);
+            mv[h] = ld_nt_load(m4 + h * kAdamThreads);
+            vv[h] = ld_nt_load(v4 + h * kAdamThreads);
         }
-        float ww[8] = {wv[0].x, wv[0].y, wv[0].z, wv[0].w, wv[1].x, wv[1].y, wv[1].z, wv[1].w};
-        float mm[8] = {mv[0].x, mv[0].y, mv[0].z, mv[0].w, mv[1].x, mv[1].y, mv[1].z, mv[1].w};
-        float v8[8] = {vv[0].x, vv[0].y, vv[0].z, vv[0].w, vv[1].x, vv[1].y, vv[1].z, vv[1].w};
 #pragma unroll
-        for (int t = 0; t < WT; ++t) {
-            if (t0 + t < a.W) {
-                const uint32_t gw[4] = {gq[t].x, gq[t].y, gq[t].z, gq[t].w};
-                const float lr_bc1 = a.lr_over_bc1[t0 + t], ibc2 = a.inv_bc2[t0 + t];
+        for (int h = 0; h < kAdamH; ++h) {
+            float ww[4] = {wv[h].x, wv[h].y, wv[h].z, wv[h].w};
+            float mm[4] = {mv[h].x, mv[h].y, mv[h].z, mv[h].w};
+            float v4_[4] = {vv[h].x, vv[h].y, vv[h].z, vv[h].w};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint32_t half = (e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu);
-                    adam_step(ww[e], mm[e], v8[e], bf16_widen(half), a.beta1, a.one_m_beta1, a.beta2,
-                              a.one_m_beta2, a.eps, lr_bc1, ibc2);
+            for (int t = 0; t < WT; ++t) {
+                if (t0 + t < a.W) {
+                    const uint32_t gw[2] = {gq[t][h].x, gq[t][h].y};
+                    const float lr_bc1 = a.lr_over_bc1[t0 + t], ibc2 = a.inv_bc2[t0 + t];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t half = (e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu);
+                        adam_step(ww[e], mm[e], v4_[e], bf16_widen(half), a.beta1, a.one_m_beta1, a.beta2,
+                                  a.one_m_beta2, a.eps, lr_bc1, ibc2);
+                    }
                 }
             }
-        }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            ld_nt_store(ld_f32x4{ww[4 * h], ww[4 * h + 1], ww[4 * h + 2], ww[4 * h + 3]}, w4 + h);
-            ld_nt_store(ld_f32x4{mm[4 * h], mm[4 * h + 1], mm[4 * h + 2], mm[4 * h + 3]}, m4 + h);
-            ld_nt_store(ld_f32x4{v8[4 * h], v8[4 * h + 1], v8[4 * h + 2], v8[4 * h + 3]}, v4 + h);
+            ld_nt_store(ld_f32x4{ww[0], ww[1], ww[2], ww[3]}, w4 + h * kAdamThreads);
+            ld_nt_store(ld_f32x4{mm[0], mm[1], mm[2], mm[3]}, m4 + h * kAdamThreads);
+            ld_nt_store(ld_f32x4{v4_[0], v4_[1], v4_[2], v4_[3]}, v4 + h * kAdamThreads);
         }
     } else {
-        // ragged tail: fewer than 8 elements left for this thread
-        for (int64_t e = e0; e < n; ++e) {
+        // the last, ragged workgroup: element by element
+        for (int64_t e = b0 + threadIdx.x; e < n; e += kAdamThreads) {
             float ww = w[e], mm = m[e], v1 = v[e];
             for (int t = t0; t < t0 + WT && t < a.W; ++t)
                 adam_step(ww, mm, v1, bf16_widen(a.grad[t][e]), a.beta1, a.one_m_beta1, a.beta2,
@@ -171,8 +185,8 @@ extern "C" ld_status ld_snapshot_layer(const void* grad_bf16, void* snap_bf16, i
     if (!ld_aligned(grad_bf16, 2) || !ld_aligned(snap_bf16, 2)) return LD_ERR_ALIGN;
     const int64_t bytes = n_elems * 2;
     const int64_t blocks = (bytes + kCopyBlockBytes - 1) / kCopyBlockBytes;
-    if (blocks > INT32_MAX) return LD_ERR_RANGE;
-    k_snapshot<<<dim3(static_cast<uint32_t>(blocks)), dim3(kCopyThreads), 0,
+    if (blocks > INT32_MAX - 8) return LD_ERR_RANGE;
+    k_snapshot<<<dim3(static_cast<uint32_t>((blocks + 7) / 8 * 8)), dim3(kCopyThreads), 0,
                  static_cast<hipStream_t>(stream)>>>(static_cast<const unsigned char*>(grad_bf16),
                                                      static_cast<unsigned char*>(snap_bf16), bytes);
     return ld_launch_status();
@@ -250,8 +264,8 @@ extern "C" ld_status ld_merge_dense_adam(float* w, float* m, float* v, int64_t n
     a.eps = eps;
     a.W = W;
     const int64_t blocks = (n + kAdamBlockElems - 1) / kAdamBlockElems;
-    if (blocks > INT32_MAX) return LD_ERR_RANGE;
-    const dim3 grid(static_cast<uint32_t>(blocks)), block(kAdamThreads);
+    if (blocks > INT32_MAX - 8) return LD_ERR_RANGE;
+    const dim3 grid(static_cast<uint32_t>((blocks + 7) / 8 * 8)), block(kAdamThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
     // steps are fused four (or eight) at a time; the state round-trips through fp32
     // memory between passes, which is exactly what it does between two calls

@@ -12,7 +12,7 @@
 //              in issue order, so the cross-diff order on an element needs no
 //              barrier.  Where a diff's records for the sub-tile start is not
 //              looked up in a table: a small kernel finds the record range of
-//              every chunk of 16 sub-tiles by binary search, the wave
+//              every chunk of 6 sub-tiles by binary search, the wave
 //              interpolates inside its chunk, loads a 128-record window a little
 //              before the guess and keeps the records that fall into its
 //              sub-tile.  The guess is checked (the window must begin before the
@@ -28,12 +28,12 @@
 namespace {
 
 constexpr int kSub = 8192;                 // elements per wave sub-tile (32 KB of LDS, 5 waves per CU)
-constexpr int kChunkSubs = 16;             // sub-tiles per chunk of the range table
+constexpr int kChunkSubs = 6;              // sub-tiles per chunk of the range table
 constexpr int64_t kChunk = static_cast<int64_t>(kSub) * kChunkSubs;
 constexpr int kGroupMax = 64;              // diffs per launch (pointer table travels as a kernel argument)
 constexpr int kWin = 2;                    // 64-record windows per diff loaded ahead
 constexpr int kPre = 10;                   // diffs whose windows are loaded before any is applied
-constexpr int kMargin = 40;                // records the window starts before the interpolated position
+constexpr int kMargin = 24;                // records the window starts before the interpolated position
 
 struct DiffTable {
     const int32_t* idx[kGroupMax];
