@@ -84,10 +84,18 @@ struct SegDesc {        // one per segment plus a sentinel
     int32_t group0;     // first group
 };
 
-struct GroupDesc {
+struct GroupDesc {      // 64 bytes: all a workgroup needs to know about its group, in one fetch
     int64_t base;       // first element of the group's first tile (multiple of 4; may precede the segment)
+    int64_t lo, hi;     // the segment's element range
+    int64_t out0;       // the segment's first output record
     int32_t seg;
-    int32_t pad;
+    int32_t k;          // records the segment keeps
+    int32_t group0;     // the segment's first group
+    int32_t ngroup;     // groups in the segment
+    uint32_t tau;       // candidate threshold (see SegState)
+    uint32_t sh;        // fine-bin shift
+    uint32_t test;      // guessed threshold
+    uint32_t pad;
 };
 
 struct SegState {       // 64 bytes
@@ -301,30 +309,14 @@ __device__ __forceinline__ uint32_t fine_bin(uint32_t key, uint32_t tau, uint32_
 
 // ------------------------------------------------------------------ geometry
 
-struct GroupRange {
-    int32_t seg;
-    int64_t base;        // first element of the group's first tile
-    int64_t lo, hi;      // the segment's element range
-    int32_t k;
-    int32_t ngroup;      // groups in the segment
-    int32_t group0;
-    int64_t out0;
-};
+typedef GroupDesc GroupRange;
 
 __device__ __forceinline__ GroupRange group_range(const Ctx& c, int32_t g) {
-    GroupRange r;
-    const GroupDesc gd = c.gdesc[g];
-    const SegDesc d = c.desc[gd.seg];
-    const SegDesc dn = c.desc[gd.seg + 1];
-    r.seg = gd.seg;
-    r.base = gd.base;
-    r.lo = d.off;
-    r.hi = dn.off;
-    r.k = d.k;
-    r.group0 = d.group0;
-    r.ngroup = dn.group0 - d.group0;
-    r.out0 = d.out0;
-    return r;
+    const ld_u32x4* p = reinterpret_cast<const ld_u32x4*>(c.gdesc + g);
+    union { ld_u32x4 q[4]; GroupDesc d; } u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) u.q[i] = p[i];
+    return u.d;
 }
 
 // Loads the 4 elements at e0..e0+3 that lie inside [lo, hi); returns the mask of
@@ -397,8 +389,6 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
     const int32_t ngroup = groups_of(off, end);
     if (threadIdx.x < sizeof(SegState) / 4) reinterpret_cast<uint32_t*>(&c.state[s])[threadIdx.x] = 0;
     for (int b = threadIdx.x; b < kBins; b += kPrepThreads) c.hist[static_cast<int64_t>(s) * kBins + b] = 0;
-    for (int32_t q = threadIdx.x; q < ngroup; q += kPrepThreads)
-        c.gdesc[d.group0 + q] = GroupDesc{align_down4(off) + static_cast<int64_t>(q) * kGroup, s, 0};
 
     // candidate threshold, guessed threshold and bin width from a sample of |r + g|
     const int64_t ns = end - off;
@@ -466,6 +456,9 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
         c.state[s].sh = binsh;
         c.state[s].test = test;
     }
+    for (int32_t q = threadIdx.x; q < ngroup; q += kPrepThreads)
+        c.gdesc[d.group0 + q] = GroupDesc{align_down4(off) + static_cast<int64_t>(q) * kGroup, off, end, d.out0,
+                                          s, k, d.group0, ngroup, tau, binsh, test, 0u};
 }
 
 // -------------------------------------------------------------------- k_main
@@ -478,17 +471,17 @@ __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __re
     __shared__ uint32_t wtot[kMainWaves];
     // consecutive workgroups go to different XCDs: each XCD streams one contiguous eighth of the tiles
     const int32_t tile = static_cast<int32_t>((blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8);
-    const GroupDesc gd = c.gdesc[tile / kTilesPerGroup];
+    const GroupDesc gd = group_range(c, tile / kTilesPerGroup);
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
     const int64_t tbase = gd.base + static_cast<int64_t>(tile % kTilesPerGroup) * kTile;
     const int64_t t = tbase + w * kMainWaveTile;
-    const int64_t seg_lo = c.desc[gd.seg].off, seg_hi = c.desc[gd.seg + 1].off;
+    const int64_t seg_lo = gd.lo, seg_hi = gd.hi;
     if (tbase >= seg_hi) {  // tile slot past the end of the segment
         if (threadIdx.x == 0) c.cnt[tile] = 0;
         return;
     }
-    const uint32_t tau = c.state[gd.seg].tau, test = c.state[gd.seg].test;
+    const uint32_t tau = gd.tau, test = gd.test;
     const bool interior = t >= seg_lo && t + kMainWaveTile <= seg_hi;
     float a[kMainRows][4];
     uint32_t mask[kMainRows];
@@ -594,9 +587,19 @@ __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __re
 // test k_main applied.
 constexpr int kTilesPerWave = kTilesPerGroup / kWaves;
 
+// Lane u < kTilesPerWave: the candidate count of the wave's tile u (k_main writes a
+// count for every tile slot of every group, 0 past the end of a segment). Fetched
+// first, so that it travels together with the group descriptor.
+__device__ __forceinline__ uint32_t wave_counts(const Ctx& c, int32_t group) {
+    const int lane = ld_lane();
+    const int32_t tile0 = group * kTilesPerGroup + static_cast<int>(threadIdx.x >> 6) * kTilesPerWave;
+    return lane < kTilesPerWave ? c.cnt[tile0 + lane] : 0u;
+}
+
 template <bool IDX, class Begin, class Item, class End>
 __device__ __forceinline__ void wave_tiles(const Ctx& c, const float* __restrict__ r, const GroupRange& gr,
-                                           int32_t group, uint32_t tau, Begin&& begin, Item&& item, End&& end) {
+                                           int32_t group, uint32_t mycnt, uint32_t tau, Begin&& begin, Item&& item,
+                                           End&& end) {
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
     const int tl0 = w * kTilesPerWave;
@@ -607,45 +610,55 @@ __device__ __forceinline__ void wave_tiles(const Ctx& c, const float* __restrict
         const int64_t nt = (gr.hi - tbase0 + kTile - 1) / kTile;
         live = nt < kTilesPerWave ? static_cast<int>(nt) : kTilesPerWave;
     }
-    const uint32_t mycnt = lane < live ? c.cnt[tile0 + lane] : 0u;
-    uint32_t x0[kTilesPerWave], x1[kTilesPerWave];
-    float v0[kTilesPerWave], v1[kTilesPerWave];
-#pragma unroll
-    for (int u = 0; u < kTilesPerWave; ++u) {
-        const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
-        const uint32_t n = cn == kOverflow ? 0u : cn;
+    // rolled loop, the next tile's slot fetched while the current one is worked on: the loop body is
+    // the whole code of the pass (a fully unrolled version spends its time fetching instructions)
+    auto fetch = [&](int u, float& a0, float& a1, uint32_t& b0, uint32_t& b1) {
+        const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u < kTilesPerWave ? u : 0, LD_WAVE));
+        const uint32_t n = (u >= live || cn == kOverflow) ? 0u : cn;
         const int64_t slot = static_cast<int64_t>(tile0 + u) * kSlot;
         const bool h0 = static_cast<uint32_t>(lane) < n, h1 = static_cast<uint32_t>(lane + LD_WAVE) < n;
-        v0[u] = h0 ? c.cval[slot + lane] : 0.0f;
-        v1[u] = h1 ? c.cval[slot + LD_WAVE + lane] : 0.0f;
-        x0[u] = (IDX && h0) ? c.cidx[slot + lane] : 0u;
-        x1[u] = (IDX && h1) ? c.cidx[slot + LD_WAVE + lane] : 0u;
-    }
-#pragma unroll
-    for (int u = 0; u < kTilesPerWave; ++u) {
-        if (u >= live) continue;
+        a0 = h0 ? c.cval[slot + lane] : 0.0f;
+        a1 = h1 ? c.cval[slot + LD_WAVE + lane] : 0.0f;
+        b0 = (IDX && h0) ? c.cidx[slot + lane] : 0u;
+        b1 = (IDX && h1) ? c.cidx[slot + LD_WAVE + lane] : 0u;
+    };
+    float v0, v1, nv0, nv1;
+    uint32_t x0, x1, nx0, nx1;
+    fetch(0, v0, v1, x0, x1);
+#pragma unroll 1
+    for (int u = 0; u < live; ++u) {
+        fetch(u + 1, nv0, nv1, nx0, nx1);
         const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
+        const bool stored = cn != kOverflow;
+        const uint32_t total = stored ? cn : static_cast<uint32_t>(kTile);
+        const int64_t slot = static_cast<int64_t>(tile0 + u) * kSlot;
+        const int64_t tbase = tbase0 + static_cast<int64_t>(u) * kTile;
         begin(u);
-        if (cn != kOverflow) {
-            if (cn > 0) item(static_cast<uint32_t>(lane) < cn, v0[u], x0[u], true);
-            if (cn > LD_WAVE) item(static_cast<uint32_t>(lane + LD_WAVE) < cn, v1[u], x1[u], true);
-            const int64_t slot = static_cast<int64_t>(tile0 + u) * kSlot;
-            for (uint32_t b0 = 2 * LD_WAVE; b0 < cn; b0 += LD_WAVE) {
-                const bool h = b0 + lane < cn;
-                const float v = h ? c.cval[slot + b0 + lane] : 0.0f;
-                const uint32_t x = (IDX && h) ? c.cidx[slot + b0 + lane] : 0u;
-                item(h, v, x, true);
-            }
-        } else {
-            const int64_t tbase = tbase0 + static_cast<int64_t>(u) * kTile;
-            for (int32_t l0 = 0; l0 < kTile; l0 += LD_WAVE) {
-                const int64_t e = tbase + l0 + lane;
+#pragma unroll 1
+        for (uint32_t b0 = 0; b0 < total; b0 += LD_WAVE) {
+            bool have = b0 + lane < total;
+            float v;
+            uint32_t x;
+            if (!stored) {
+                const int64_t e = tbase + b0 + lane;
                 const bool in = e >= gr.lo && e < gr.hi;
-                const float v = in ? r[e] : 0.0f;
-                item(in && ld_key(v) >= tau, v, static_cast<uint32_t>(l0 + lane), false);
+                v = in ? r[e] : 0.0f;
+                x = b0 + lane;
+                have = in && ld_key(v) >= tau;
+            } else if (b0 == 0) {
+                v = v0;
+                x = x0;
+            } else if (b0 == LD_WAVE) {
+                v = v1;
+                x = x1;
+            } else {
+                v = have ? c.cval[slot + b0 + lane] : 0.0f;
+                x = (IDX && have) ? c.cidx[slot + b0 + lane] : 0u;
             }
+            item(have, v, x, stored);
         }
         end(u);
+        v0 = nv0; v1 = nv1; x0 = nx0; x1 = nx1;
     }
 }
 
@@ -670,20 +683,21 @@ __device__ __forceinline__ GroupRange seg_range(const Ctx& c, int32_t s) {
     r.group0 = d.group0;
     r.ngroup = dn.group0 - d.group0;
     r.out0 = d.out0;
+    r.tau = r.sh = r.test = r.pad = 0;
     return r;
 }
 
 // Fine-bin histogram of the candidates of one group, added to the segment's.
 __global__ __launch_bounds__(kThreads) void k_hist(const float* __restrict__ r, Ctx c) {
     __shared__ uint32_t lh[kBins];
+    const uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
     if (gr.k == 0) return;
-    const SegState* st = c.state + gr.seg;
-    const uint32_t tau = st->tau, binsh = st->sh;
+    const uint32_t tau = gr.tau, binsh = gr.sh;
     for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
     __syncthreads();
     wave_tiles<false>(
-        c, r, gr, blockIdx.x, tau, [](int) {},
+        c, r, gr, blockIdx.x, mycnt, tau, [](int) {},
         [&](bool have, float v, uint32_t, bool) {
             if (have) atomicAdd(&lh[fine_bin(ld_key(v), tau, binsh)], 1u);
         },
@@ -717,10 +731,11 @@ __global__ __launch_bounds__(kThreads) void k_bin(Ctx c) {
 // are gathered per segment.
 __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r, Ctx c) {
     __shared__ uint32_t wsum[kWaves];
+    const uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
     SegState* st = c.state + gr.seg;
     if (gr.k == 0 || st->mode != kModeCand) return;
-    const uint32_t tau = st->tau, binsh = st->sh, b1 = st->prefix;
+    const uint32_t tau = gr.tau, binsh = gr.sh, b1 = st->prefix;
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
     uint32_t* gkey = c.gkey + static_cast<int64_t>(gr.seg) * kGatherCap;
@@ -729,7 +744,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     uint32_t wave_gt = 0, gt = 0, mine = 0;  // lane u keeps the count of the wave's tile u
     int32_t tile_of_item = 0;
     wave_tiles<false>(
-        c, r, gr, blockIdx.x, tau,
+        c, r, gr, blockIdx.x, mycnt, tau,
         [&](int u) {
             gt = 0;
             tile_of_item = tile0 + u;
@@ -843,17 +858,18 @@ __global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
 __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_t* __restrict__ out_idx,
                                                    float* __restrict__ out_val, Ctx c) {
     __shared__ uint32_t tile_out[kTilesPerGroup], tile_eqb[kTilesPerGroup];
+    const uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
     const SegState* st = c.state + gr.seg;
     if (gr.k == 0) return;
-    const uint32_t tau = st->tau, test = st->test, T = st->prefix, m = st->krem;
+    const uint32_t tau = gr.tau, test = gr.test, T = st->prefix, m = st->krem;
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
     const int tl0 = w * kTilesPerWave;
     int64_t tbase = 0;
     if (st->mode != kModeCand) {
         wave_tiles<true>(
-            c, r, gr, blockIdx.x, tau,
+            c, r, gr, blockIdx.x, mycnt, tau,
             [&](int u) { tbase = gr.base + static_cast<int64_t>(tl0 + u) * kTile; },
             [&](bool have, float v, uint32_t local, bool stored) {
                 if (have && stored && ld_key(v) >= test) r[tbase + local] = v;
@@ -874,7 +890,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     uint32_t run_out = 0;  // records of the segment emitted before this point
     uint32_t run_eq = 0;   // ties seen before this point
     wave_tiles<true>(
-        c, r, gr, blockIdx.x, tau,
+        c, r, gr, blockIdx.x, mycnt, tau,
         [&](int u) {
             run_out = tile_out[tl0 + u];
             run_eq = tile_eqb[tl0 + u];
