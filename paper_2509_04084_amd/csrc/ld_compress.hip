@@ -58,17 +58,14 @@ constexpr int kGroup = kTile * kTilesPerGroup;    // 262144 elements per small-p
 constexpr int kBins = 2048;
 constexpr int kTopBin = kBins - 1;
 constexpr int kShift1 = 20, kShift2 = 9;          // radix digits: [30:20] [19:9] [8:0]
-constexpr int kPrepThreads = 1024;
-#ifndef LD_SAMPLE_ITEMS
-#define LD_SAMPLE_ITEMS 16
+#ifndef LD_PREP_THREADS
+#define LD_PREP_THREADS 512
 #endif
-#ifndef LD_SAMPLE_Z
-#define LD_SAMPLE_Z 6.5f
-#endif
-constexpr int kSampleItems = LD_SAMPLE_ITEMS;
-constexpr int kSample = kPrepThreads * kSampleItems;  // 16384 sampled elements per segment
+constexpr int kPrepThreads = LD_PREP_THREADS;
+constexpr int kSample = 16384;                        // sampled elements per segment
+constexpr int kSampleItems = kSample / kPrepThreads;
 constexpr int kSampleRuns = kSample / LD_WAVE;        // as 256 runs of 64 consecutive elements
-constexpr float kSampleZ = LD_SAMPLE_Z;                  // safety margin of the rank estimate, in sigmas
+constexpr float kSampleZ = 6.5f;                  // safety margin of the rank estimate, in sigmas
 constexpr int kGatherCap = 4096;                  // keys of the threshold bin, per segment
 constexpr int kGatherItems = kGatherCap / kThreads;
 constexpr int kSegPerLaunch = 448;
@@ -406,8 +403,8 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
                 e = off + i * kPrepThreads + threadIdx.x;
             } else {
                 const int run = i * (kPrepThreads / LD_WAVE) + (threadIdx.x >> 6);
-                const int64_t jitter = hash32(static_cast<uint32_t>(run) * 2654435761u + static_cast<uint32_t>(s)) %
-                                       static_cast<uint32_t>(stride - LD_WAVE + 1);
+                const int64_t jitter = __umulhi(hash32(static_cast<uint32_t>(run) * 2654435761u + static_cast<uint32_t>(s)),
+                                                static_cast<uint32_t>(stride - LD_WAVE + 1));
                 e = off + run * stride + jitter + lane;
             }
             key[i] = 0;
@@ -419,31 +416,34 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
         // Sample ranks (1 = largest). The selected keys are rounded down to 2^kShift2, which only
         // adds a few candidates.
         uint32_t rank[3], sel[3];
+        bool estimate = true;
         if (whole) {
             // the sample is the segment: the exact threshold lies in [tau, tau + 2^kShift2); every key
             // above that range is certainly selected; bins of width 1
             rank[0] = rank[1] = rank[2] = static_cast<uint32_t>(k);
-            block_select_multi<kPrepThreads, kSampleItems, 3>(key, valid, rank, lh, sh, res, sel);
-            tau = sel[0];
-            test = tau + (1u << kShift2);
         } else {
             // expected sample hits a = k * kSample / ns. Candidates: sample rank x with x = a + z*sqrt(x),
-            // so that fewer than k elements at or above tau is a z-sigma event.
+            // so that fewer than k elements at or above tau is a z-sigma event. Bins span [tau, hi]
+            // where hi is the sample key at rank a - z*sqrt(a): the k-th largest key lies below it, in
+            // a fine bin, except in a z-sigma event.
             const float a = static_cast<float>(k) * (static_cast<float>(kSample) / static_cast<float>(ns));
             const float sq = 0.5f * (kSampleZ + sqrtf(kSampleZ * kSampleZ + 4.0f * a));
             rank[0] = static_cast<uint32_t>(sq * sq) + 2u;
-            if (rank[0] >= static_cast<uint32_t>(kSample)) {
-                tau = 0;  // k too large for an estimate: everything is a candidate, nothing is pre-zeroed
-                binsh = kShift1;
+            const float lo_rank = a - kSampleZ * sqrtf(a);
+            rank[2] = lo_rank > 1.0f ? static_cast<uint32_t>(lo_rank) : 1u;
+            const uint32_t mid = static_cast<uint32_t>(a + 0.5f);
+            rank[1] = mid < rank[2] ? rank[2] : (mid > rank[0] ? rank[0] : mid);
+            estimate = rank[0] < static_cast<uint32_t>(kSample);
+        }
+        if (!estimate) {
+            tau = 0;  // k too large for an estimate: everything is a candidate, nothing is pre-zeroed
+            binsh = kShift1;
+        } else {
+            block_select_multi<kPrepThreads, kSampleItems, 3>(key, valid, rank, lh, sh, res, sel);
+            tau = sel[0];
+            if (whole) {
+                test = tau + (1u << kShift2);
             } else {
-                // bins span [tau, hi] where hi is the sample key at rank a - z*sqrt(a): the k-th
-                // largest key lies below it, in a fine bin, except in a z-sigma event
-                const float lo_rank = a - kSampleZ * sqrtf(a);
-                rank[2] = lo_rank > 1.0f ? static_cast<uint32_t>(lo_rank) : 1u;
-                const uint32_t mid = static_cast<uint32_t>(a + 0.5f);
-                rank[1] = mid < rank[2] ? rank[2] : (mid > rank[0] ? rank[0] : mid);
-                block_select_multi<kPrepThreads, kSampleItems, 3>(key, valid, rank, lh, sh, res, sel);
-                tau = sel[0];
                 test = sel[1];
                 const uint32_t range = (sel[2] | ((1u << kShift2) - 1u)) - tau;
                 while ((range >> binsh) > static_cast<uint32_t>(kTopBin - 1)) ++binsh;

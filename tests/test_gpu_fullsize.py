@@ -1,0 +1,150 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The CPU oracle cannot redo 1.56 G (or 6.74 G) elements in seconds, so at these
+sizes the checks are:
+  * properties that hold at any size, evaluated on the whole output (record
+    counts and order, index ranges, residual + scattered values == r + g bit for
+    bit, no unselected magnitude above a selected one);
+  * the oracle itself on sampled segments / slices / layers, element by element
+    (bit-exact for the sparse path, the Adam tolerance for the dense one).
+Inputs are the benchmark's own seeded generators (synth.py), drawn on the GPU.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_04084_amd import lowdiff as ld
+from paper_2509_04084_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+def _progress(msg):
+    print(f"[fullsize] {msg}", flush=True)
+
+
+def test_gpt2xl_compress_and_merge_full_size():
+    wl = synth.workload("gpt2xl")
+    off, k = wl.seg_off, wl.seg_k
+    n, n_seg = wl.n, len(wl.sizes)
+    K = int(k.astype(np.int64).sum())
+    W = 3  # diffs built here (the benchmark chains 20 the same way)
+    out0 = np.concatenate([[0], np.cumsum(k.astype(np.int64))])
+    # segments redone by the oracle: the first small ones, one of every size class, the last
+    sample = sorted({1, 2, 3, 4, 5, 6, 10, 12, 13, n_seg - 3, n_seg - 2, n_seg - 1})
+    r = torch.zeros(n, device=DEV)
+    ws = torch.empty(ld.ld_compress_topk_workspace(off), dtype=torch.uint8, device=DEV)
+    seg_of_rec = torch.repeat_interleave(torch.arange(n_seg, device=DEV), torch.from_numpy(k.astype(np.int64)).to(DEV))
+    off_t = torch.from_numpy(off).to(DEV)
+    idxs, vals = [], []
+    for t in range(W):
+        _progress(f"compress t={t}")
+        g = synth.gradient(wl, t, device=DEV)
+        r_before = r.clone()
+        idx, val = ld.ld_compress_topk(g, r, off, k, workspace=ws)
+        torch.cuda.synchronize()
+        idxs.append(idx)
+        vals.append(val)
+        # --- whole-output properties
+        assert idx.numel() == K and val.numel() == K
+        i64 = idx.to(torch.int64)
+        assert bool((i64[1:] > i64[:-1]).all()), "records not strictly ascending"
+        assert bool((i64 >= off_t[seg_of_rec]).all()) and bool((i64 < off_t[seg_of_rec + 1]).all()), \
+            "a record lies outside its segment"
+        a = r_before + g  # one fp32 add per element, as the definition says
+        assert bool((r[i64] == 0).all()) and not bool(torch.signbit(r[i64]).any()), "selected residual not +0"
+        assert torch.equal(val.view(torch.int32), a[i64].view(torch.int32)), "val is not r+g bit for bit"
+        rest = a.clone()
+        rest[i64] = 0.0
+        assert torch.equal(rest.view(torch.int32), r.view(torch.int32)), "unselected residual is not r+g"
+        # no unselected magnitude exceeds the smallest selected one of its segment
+        min_sel = torch.full((n_seg,), float("inf"), device=DEV).scatter_reduce(
+            0, seg_of_rec, val.abs(), reduce="amin", include_self=True)
+        for s in range(n_seg):
+            lo, hi = int(off[s]), int(off[s + 1])
+            assert float(r[lo:hi].abs().max()) <= float(min_sel[s]), f"segment {s}: threshold violated"
+        del rest, a
+        # --- oracle on sampled segments
+        for s in sample:
+            lo, hi = int(off[s]), int(off[s + 1])
+            oi, ov, orr = oracle.topk_ef(g[lo:hi].cpu().numpy(), r_before[lo:hi].cpu().numpy(),
+                                         np.array([0, hi - lo], np.int64), k[s:s + 1], select=True)
+            o0, o1 = int(out0[s]), int(out0[s + 1])
+            np.testing.assert_array_equal(idx[o0:o1].cpu().numpy(), oi + lo, err_msg=f"idx seg {s} t={t}")
+            np.testing.assert_array_equal(bits(val[o0:o1].cpu().numpy()), bits(ov), err_msg=f"val seg {s} t={t}")
+            np.testing.assert_array_equal(bits(r[lo:hi].cpu().numpy()), bits(orr), err_msg=f"residual seg {s} t={t}")
+        del g, r_before
+    # --- merge of the window, checked by the oracle on slices of w
+    _progress("merge")
+    w = synth.base_weights(n, device=DEV, std=wl.w_std)
+    slices = [(0, 3_000_000), (int(off[3]) - 1_000_000, int(off[3]) + 2_000_000),
+              (n // 2 - 1_234_567, n // 2 + 1_000_000), (n - 2_500_001, n)]
+    before = [w[a:b].cpu().numpy() for a, b in slices]
+    ld.ld_merge_sparse(w, idxs, vals, wl.lr)
+    torch.cuda.synchronize()
+    idx_h = [i.cpu().numpy() for i in idxs]
+    val_h = [v.cpu().numpy() for v in vals]
+    for (a, b), w0 in zip(slices, before):
+        sub_i, sub_v = [], []
+        for ih, vh in zip(idx_h, val_h):
+            p0, p1 = np.searchsorted(ih, a), np.searchsorted(ih, b)
+            sub_i.append((ih[p0:p1] - a).astype(np.int32))
+            sub_v.append(vh[p0:p1])
+        ref = oracle.merge_sparse(w0, sub_i, sub_v, wl.lr)
+        np.testing.assert_array_equal(bits(w[a:b].cpu().numpy()), bits(ref), err_msg=f"merge slice [{a},{b})")
+    # untouched elements keep their bits; touched ones moved: count of changed == size of the union
+    _progress("merge: untouched elements")
+    w_ref = synth.base_weights(n, device=DEV, std=wl.w_std)
+    touched = torch.zeros(n, dtype=torch.bool, device=DEV)
+    for i in idxs:
+        touched[i.to(torch.int64)] = True
+    assert torch.equal(w[~touched].view(torch.int32), w_ref[~touched].view(torch.int32))
+
+
+def test_llama7b_snapshot_and_adam_full_size():
+    wl = synth.workload("llama7b")
+    off = wl.seg_off
+    n, W = wl.n, wl.window
+    layers = [(int(off[s]), int(off[s + 1])) for s in range(len(wl.sizes))]
+    checked = [0, 1, 5, 7, 8, 9, len(layers) - 2, len(layers) - 1]  # embedding, attn, mlp, norms, final norm, head
+    _progress("generating the gradients")
+    src = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    snaps = [torch.empty(n, dtype=torch.bfloat16, device=DEV) for _ in range(W)]
+    for t in range(W):
+        for s, (lo, hi) in enumerate(layers):
+            src[lo:hi] = synth.gradient_layer_bf16(wl, t, s, DEV)
+        # layer-wise snapshot, last layer first (backward order), as the benchmark does
+        for lo, hi in reversed(layers):
+            ld.ld_snapshot_layer(src[lo:hi], snaps[t][lo:hi])
+        torch.cuda.synchronize()
+        assert torch.equal(src.view(torch.int16), snaps[t].view(torch.int16)), f"snapshot {t} differs"
+    del src
+    _progress("adam replay")
+    w = synth.base_weights(n, device=DEV, std=wl.w_std)
+    m = torch.zeros(n, device=DEV)
+    v = torch.zeros(n, device=DEV)
+    sl = []
+    for s in checked:
+        lo, hi = layers[s]
+        hi = min(hi, lo + 3_000_000)
+        sl.append((lo, hi, w[lo:hi].cpu().numpy(), m[lo:hi].cpu().numpy(), v[lo:hi].cpu().numpy()))
+    # two calls: step0 = 0 and step0 = W, as consecutive benchmark steps do
+    ld.ld_merge_dense_adam(w, m, v, snaps, 0, wl.lr, **synth.ADAM)
+    ld.ld_merge_dense_adam(w, m, v, snaps, W, wl.lr, **synth.ADAM)
+    torch.cuda.synchronize()
+    for lo, hi, w0, m0, v0 in sl:
+        gs = [sn[lo:hi].view(torch.int16).cpu().numpy().view(np.uint16) for sn in snaps]
+        wr, mr, vr = oracle.adam_replay(w0, m0, v0, gs + gs, 0, wl.lr, **synth.ADAM)
+        for name, got, ref in (("w", w, wr), ("m", m, mr), ("v", v, vr)):
+            x = got[lo:hi].cpu().numpy()
+            assert np.all(np.abs(x - ref) <= 1e-7 + 1e-6 * np.abs(ref)), f"{name} layer slice [{lo},{hi})"
+        xv = v[lo:hi].cpu().numpy()
+        assert np.all(np.abs(xv - vr) <= 2e-6 * np.abs(vr)), f"v relative, slice [{lo},{hi})"
+    # every element moved by a finite amount (no slice skipped by the launch shape)
+    assert bool(torch.isfinite(w).all()) and bool((v > 0).sum() > 0.99 * n)
