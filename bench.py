@@ -150,15 +150,46 @@ class DenseLeg:
         return 2 * self.n * self.W
 
 
-def cpu_baseline(budget_hint_s=20.0):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+class CopyCal:
+    """A plain copy of known size (1 GiB in, 1 GiB out) through ld_snapshot_layer: the yardstick the
+    FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by."""
+
+    def __init__(self, dev):
+        self.n = 1 << 29  # bf16 elements
+        self.src = torch.randint(-30000, 30000, (self.n,), dtype=torch.int16, device=dev).view(torch.bfloat16)
+        self.dst = torch.empty_like(self.src)
+
+    def step(self, tm):
+        tok = tm.start("copycal")
+        ld.ld_snapshot_layer(self.src, self.dst)
+        tm.stop(tok)
+
+
+def measured_traffic(path):
+    """HBM bytes per call from the committed counter summary (lines 'traffic <entry> <bytes>')."""
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic":
+                    out[parts[1]] = int(float(parts[2]))
+    except OSError:
+        pass
+    return out
+
+
+def cpu_baseline():
+    """The CPU oracle, as it stands (single thread), on a bounded sample of the same workload:
+    about 10-20 s of host work, extrapolated to the full step by gradient bytes."""
     import oracle
     xl, ll = synth.workload("gpt2xl"), synth.workload("llama7b")
-    segs = [4, 10, 12]  # one block's qkv, fc and proj weights: 7.68 M + 10.24 M + 10.24 M elements
+    # sparse: the four weight matrices of two transformer blocks (61 M elements), 10 chained diffs
+    segs = [4, 6, 10, 12, 16, 18, 22, 24]
     sizes = [xl.sizes[s] for s in segs]
     off, k = synth.seg_offsets(sizes), synth.seg_topk(sizes, *xl.rho)
     n = int(off[-1])
-    Wc = 4
+    Wc = 10
     grads = []
     for t in range(Wc):
         g = np.empty(n, np.float32)
@@ -176,15 +207,21 @@ def cpu_baseline(budget_hint_s=20.0):
     oracle.merge_sparse(w0, idxs, vals, xl.lr)
     t_sparse = time.perf_counter() - t0
     sparse_bytes = 4 * n * Wc
-    # dense: one attention projection layer (16.8 M elements), W = 4
-    nd, Wd = ll.sizes[1], ll.window
-    gs = [synth.gradient_layer_bf16(ll, t, 1, "cpu").view(torch.int16).numpy().view(np.uint16) for t in range(Wd)]
-    wd = synth.base_weights(nd).numpy()
-    z = np.zeros(nd, np.float32)
-    t0 = time.perf_counter()
-    snaps = [oracle.snapshot(g) for g in gs]
-    oracle.adam_replay(wd, z, z, snaps, 0, ll.lr, **synth.ADAM)
-    t_dense = time.perf_counter() - t0
+    del grads
+    # dense: the seven weight matrices of the first block (202 M elements), W = 4
+    dsegs = [1, 2, 3, 4, 5, 6, 7]
+    Wd = ll.window
+    t_dense, nd = 0.0, 0
+    for s in dsegs:
+        ns = ll.sizes[s]
+        gs = [synth.gradient_layer_bf16(ll, t, s, "cpu").view(torch.int16).numpy().view(np.uint16) for t in range(Wd)]
+        wd = synth.base_weights(ns).numpy()
+        z = np.zeros(ns, np.float32)
+        t0 = time.perf_counter()
+        snaps = [oracle.snapshot(g) for g in gs]
+        oracle.adam_replay(wd, z, z, snaps, 0, ll.lr, **synth.ADAM)
+        t_dense += time.perf_counter() - t0
+        nd += ns
     dense_bytes = 2 * nd * Wd
     # weight the two legs as the full step does (gradient bytes of each leg)
     full_sparse = 4 * xl.n * xl.window
@@ -194,7 +231,7 @@ def cpu_baseline(budget_hint_s=20.0):
     return {
         "value": value, "unit": "GB/s (gradient bytes)", "cores": 1, "kind": "oracle",
         "sample": (f"gpt2xl segments {segs} ({n:,} elements), {Wc} chained top-k (nth_element variant) + "
-                   f"window merge: {t_sparse:.2f} s; llama7b layer 1 ({nd:,} elements), snapshot + Adam "
+                   f"window merge: {t_sparse:.2f} s; llama7b layers {dsegs} ({nd:,} elements), snapshot + Adam "
                    f"replay W={Wd}: {t_dense:.2f} s; extrapolated to the full step by gradient bytes"),
         "sparse_GBps": sparse_bytes / t_sparse / 1e9, "dense_GBps": dense_bytes / t_dense / 1e9,
     }
@@ -208,7 +245,8 @@ def main():
     ap.add_argument("--pool", type=int, default=10, help="distinct gradients cycled by the sparse leg")
     ap.add_argument("--sparse", default="gpt2xl")
     ap.add_argument("--dense", default="llama7b")
-    ap.add_argument("--legs", default="sparse,dense")
+    ap.add_argument("--legs", default="sparse,dense",
+                    help="comma list of sparse, dense, copycal (copycal: a 1 GiB plain copy, for counter calibration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -222,6 +260,7 @@ def main():
     t_setup = time.perf_counter()
     sparse = SparseLeg(synth.workload(args.sparse), dev, args.pool) if "sparse" in legs else None
     dense = DenseLeg(synth.workload(args.dense), dev) if "dense" in legs else None
+    copycal = CopyCal(dev) if "copycal" in legs else None
     torch.cuda.synchronize()
     log(f"[setup] {time.perf_counter() - t_setup:.1f} s, {torch.cuda.memory_allocated() / 1e9:.1f} GB resident")
 
@@ -230,6 +269,8 @@ def main():
             sparse.step(tm)
         if dense:
             dense.step(tm)
+        if copycal:
+            copycal.step(tm)
 
     for i in range(args.warmup):
         one_step(Timer())
@@ -270,10 +311,20 @@ def main():
     if dense:
         share["ld_snapshot_layer(x291)"] = per["snapshot_iter"] * dense.W
         share["ld_merge_dense_adam"] = per["adam"]
+    if copycal:
+        calls["copycal(ld_snapshot_layer, 1 GiB)"] = roof("copycal", 4 * copycal.n)
+    if not share:
+        print(json.dumps({"calls": calls}), flush=True)
+        return
     dom = max(share, key=share.get)
+    traffic = measured_traffic(os.path.join(ROOT, "profiles", "hbm_traffic_gpt2xl_llama7b.txt"))
+    for name, c in calls.items():
+        c["traffic_bytes"] = traffic.get(name.split("(")[0])
     roofline = {"bound": "hbm", "kernel": dom, "achieved": calls[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": calls[dom]["frac"], "traffic": None,
-                "note": "per call of the entry point (all its kernels), HIP events on the launch stream"}
+                "unit": "GB/s", "frac": calls[dom]["frac"], "traffic": calls[dom]["traffic_bytes"],
+                "note": "per call of the entry point (all its kernels), HIP events on the launch stream; "
+                        "traffic = HBM bytes per call from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by "
+                        "what the same counter reads for a 1 GiB plain copy (profiles/)"}
     out = {
         "metric": "diff-build GB/s + merge GB/s (grad bytes), % of MI355X HBM roofline",
         "value": value, "unit": "GB/s (gradient bytes)", "n_gpus": 1, "steps": args.steps,
