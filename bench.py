@@ -7,8 +7,10 @@ One step = one pass of the whole hot path over one batch of synthetic gradients:
       W = 20 chained ld_compress_topk calls (error-feedback residual carried from
       call to call) followed by one ld_merge_sparse of the 20-diff window;
   dense leg (Llama-7B-shaped, 6.74 B parameters, fp32 w/m/v, bf16 gradients):
-      W = 4 iterations of layer-wise ld_snapshot_layer (291 layers each) followed
-      by one fused ld_merge_dense_adam of the 4 snapshots.
+      W = 4 iterations of layer-wise snapshots - one ld_snapshot_layers call per model
+      layer as its gradient becomes available in the backward pass (head + final norm,
+      32 transformer layers of 9 tensors each, embedding: 34 calls, 291 tensors) -
+      followed by one fused ld_merge_dense_adam of the 4 snapshots.
 
 All inputs are resident in HBM before the timed region.  State (residual, w, m, v)
 is carried from step to step, as in training: nothing is restored inside the
@@ -120,9 +122,15 @@ class DenseLeg:
         self.m = torch.zeros(self.n, dtype=torch.float32, device=dev)
         self.v = torch.zeros(self.n, dtype=torch.float32, device=dev)
         self.layers = [(int(self.off[s]), int(self.off[s + 1])) for s in range(len(wl.sizes))]
-        # backward order: last layer's gradient exists first
-        self.src_views = [[g[lo:hi] for lo, hi in reversed(self.layers)] for g in self.src]
-        self.snap_views = [[g[lo:hi] for lo, hi in reversed(self.layers)] for g in self.snap]
+        # model layers: embedding | 32 x (q, k, v, o, gate, up, down, 2 norms) | final norm + head;
+        # backward order: the last layer's gradient exists first
+        nt = len(self.layers)
+        groups = [[0]] + [list(range(1 + 9 * b, 10 + 9 * b)) for b in range((nt - 3) // 9)] + [[nt - 2, nt - 1]]
+        self.groups = list(reversed(groups))
+        self.src_views = [[[g[self.layers[s][0]:self.layers[s][1]] for s in grp] for grp in self.groups]
+                          for g in self.src]
+        self.snap_views = [[[g[self.layers[s][0]:self.layers[s][1]] for s in grp] for grp in self.groups]
+                           for g in self.snap]
         self.step0 = 0
         self.it = 0
 
@@ -132,7 +140,7 @@ class DenseLeg:
             dv = self.snap_views[t]
             tok = tm.start("snapshot_iter")
             for a, b in zip(sv, dv):
-                ld.ld_snapshot_layer(a, b)
+                ld.ld_snapshot_layers(a, b)
             tm.stop(tok)
             self.it += 1
         tok = tm.start("adam")
@@ -301,7 +309,7 @@ def main():
         calls["ld_compress_topk"]["grad_GBps"] = 4 * sparse.n / (per["compress"] * 1e-3) / 1e9
         calls["ld_merge_sparse"]["grad_GBps"] = 4 * sparse.n * sparse.W / (per["merge_sparse"] * 1e-3) / 1e9
     if dense:
-        calls["ld_snapshot_layer(x291)"] = roof("snapshot_iter", dense.bytes_snapshot_iter())
+        calls["ld_snapshot_layers(x34)"] = roof("snapshot_iter", dense.bytes_snapshot_iter())
         calls["ld_merge_dense_adam"] = roof("adam", dense.bytes_adam())
     # the call that takes the largest share of the step
     share = {}
@@ -309,7 +317,7 @@ def main():
         share["ld_compress_topk"] = per["compress"] * sparse.W
         share["ld_merge_sparse"] = per["merge_sparse"]
     if dense:
-        share["ld_snapshot_layer(x291)"] = per["snapshot_iter"] * dense.W
+        share["ld_snapshot_layers(x34)"] = per["snapshot_iter"] * dense.W
         share["ld_merge_dense_adam"] = per["adam"]
     if copycal:
         calls["copycal(ld_snapshot_layer, 1 GiB)"] = roof("copycal", 4 * copycal.n)
@@ -335,7 +343,7 @@ def main():
                    "sparse": (f"{args.sparse}: n={sparse.n} segs={len(sparse.wl.sizes)} rho=1% W={sparse.W} "
                               f"chained compress + window merge") if sparse else None,
                    "dense": (f"{args.dense}: n={dense.n} layers={len(dense.wl.sizes)} W={dense.W} "
-                             f"layer snapshots + fused Adam replay") if dense else None},
+                             f"snapshots per model layer ({len(dense.groups)} calls) + fused Adam replay") if dense else None},
         "roofline": roofline, "calls": calls,
     }
     if not args.no_cpu_baseline:

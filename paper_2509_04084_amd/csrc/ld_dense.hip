@@ -67,8 +67,11 @@ __global__ __launch_bounds__(kCopyThreads) void k_snapshot(const unsigned char* 
 
 __global__ __launch_bounds__(kCopyThreads) void k_snapshot_batch(CopyBatch cb) {
     // which layer does this block belong to: binary search in the block prefix
+    // consecutive workgroups go to different XCDs: each XCD copies one contiguous eighth of the launch
+    const int32_t per = (static_cast<int32_t>(gridDim.x) + 7) / 8;
+    const int32_t blk = static_cast<int32_t>(blockIdx.x % 8) * per + static_cast<int32_t>(blockIdx.x / 8);
+    if (blk >= cb.first_block[cb.n]) return;
     int lo = 0, hi = cb.n;
-    const int32_t blk = blockIdx.x;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (cb.first_block[mid] <= blk) lo = mid; else hi = mid;
@@ -225,7 +228,7 @@ extern "C" ld_status ld_snapshot_layers(const void* const* src, void* const* dst
             cb.job[j] = CopyJob{nullptr, nullptr, 0};
             cb.first_block[j + 1] = cb.first_block[cb.n];
         }
-        k_snapshot_batch<<<dim3(static_cast<uint32_t>(blocks)), dim3(kCopyThreads), 0,
+        k_snapshot_batch<<<dim3(static_cast<uint32_t>((blocks + 7) / 8 * 8)), dim3(kCopyThreads), 0,
                            static_cast<hipStream_t>(stream)>>>(cb);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     }

@@ -119,9 +119,14 @@ def test_llama7b_snapshot_and_adam_full_size():
     for t in range(W):
         for s, (lo, hi) in enumerate(layers):
             src[lo:hi] = synth.gradient_layer_bf16(wl, t, s, DEV)
-        # layer-wise snapshot, last layer first (backward order), as the benchmark does
-        for lo, hi in reversed(layers):
-            ld.ld_snapshot_layer(src[lo:hi], snaps[t][lo:hi])
+        # one call per model layer (embedding | 32 x 9 tensors | final norm + head), last layer first
+        # (backward order), as the benchmark does
+        nt = len(layers)
+        groups = [[0]] + [list(range(1 + 9 * b, 10 + 9 * b)) for b in range((nt - 3) // 9)] + [[nt - 2, nt - 1]]
+        assert sorted(sum(groups, [])) == list(range(nt))
+        for grp in reversed(groups):
+            ld.ld_snapshot_layers([src[layers[s][0]:layers[s][1]] for s in grp],
+                                  [snaps[t][layers[s][0]:layers[s][1]] for s in grp])
         torch.cuda.synchronize()
         assert torch.equal(src.view(torch.int16), snaps[t].view(torch.int16)), f"snapshot {t} differs"
     del src
