@@ -66,8 +66,8 @@ constexpr int kSample = 16384;                        // sampled elements per se
 constexpr int kSampleItems = kSample / kPrepThreads;
 constexpr int kSampleRuns = kSample / LD_WAVE;        // as 256 runs of 64 consecutive elements
 constexpr float kSampleZ = 6.5f;                  // safety margin of the rank estimate, in sigmas
-constexpr int kGatherCap = 4096;                  // keys of the threshold bin, per segment
-constexpr int kGatherItems = kGatherCap / kThreads;
+constexpr int kGatherBase = 4096;                 // gather list of a segment: kGatherBase + n_s / kGatherPer keys
+constexpr int kGatherPer = 4096;
 constexpr int kSegPerLaunch = 448;
 constexpr int kFullGrid = 1024;                   // workgroups of the (normally idle) k_full_* kernels
 constexpr uint32_t kModeCand = 0, kModeFull = 1;
@@ -138,6 +138,15 @@ struct UploadBatch {
 };
 
 __host__ __device__ inline int64_t align_down4(int64_t x) { return x & ~static_cast<int64_t>(3); }
+
+// Gather list of segment s = [lo, hi): first entry and capacity. Derived from the offsets alone,
+// so that no table is needed: capacity >= kGatherBase + (hi - lo) / kGatherPer - 1.
+__host__ __device__ inline int64_t gather_first(int32_t s, int64_t lo) {
+    return static_cast<int64_t>(kGatherBase) * s + lo / kGatherPer;
+}
+__host__ __device__ inline uint32_t gather_cap(int64_t lo, int64_t hi) {
+    return static_cast<uint32_t>(kGatherBase + hi / kGatherPer - lo / kGatherPer);
+}
 
 __host__ __device__ inline int32_t groups_of(int64_t off, int64_t end) {
     if (end <= off) return 0;
@@ -217,34 +226,6 @@ __device__ __forceinline__ void flush_hist(uint32_t* h, const uint32_t* lh) {
         const uint32_t x = lh[b];
         if (x) atomicAdd(h + b, x);
     }
-}
-
-// Key at rank `rank` (1 = largest) among the valid keys the NT threads hold in
-// registers: three-level radix select with an LDS histogram. Returns the key;
-// *ties = how many keys equal to it belong to the `rank` largest.
-template <int NT, int ITEMS>
-__device__ uint32_t block_select(const uint32_t (&key)[ITEMS], uint32_t valid_mask, uint32_t rank,
-                                 uint32_t* lh, uint32_t* sh, uint32_t* res, uint32_t* ties) {
-    uint32_t prefix = 0, krem = rank;
-#pragma unroll 1
-    for (int level = 0; level < 3; ++level) {
-        const int match_shift = (level == 0) ? 31 : (level == 1 ? kShift1 : kShift2);
-        const int digit_shift = (level == 0) ? kShift1 : (level == 1 ? kShift2 : 0);
-        const uint32_t digit_mask = (level == 2) ? 0x1FFu : 0x7FFu;
-        for (int b = threadIdx.x; b < kBins; b += NT) lh[b] = 0;
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i)
-            if (((valid_mask >> i) & 1u) && (key[i] >> match_shift) == (prefix >> match_shift))
-                atomicAdd(&lh[(key[i] >> digit_shift) & digit_mask], 1u);
-        __syncthreads();
-        find_bin<NT, false>(lh, krem, sh, res);
-        prefix |= res[0] << digit_shift;
-        krem = res[1];
-        __syncthreads();
-    }
-    *ties = krem;
-    return prefix;
 }
 
 // The keys at R ranks (1 = largest), each rounded DOWN to a multiple of
@@ -738,8 +719,9 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     const uint32_t tau = gr.tau, binsh = gr.sh, b1 = st->prefix;
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
-    uint32_t* gkey = c.gkey + static_cast<int64_t>(gr.seg) * kGatherCap;
-    int32_t* gtile = c.gtile + static_cast<int64_t>(gr.seg) * kGatherCap;
+    uint32_t* gkey = c.gkey + gather_first(gr.seg, gr.lo);
+    int32_t* gtile = c.gtile + gather_first(gr.seg, gr.lo);
+    const uint32_t gcap = gather_cap(gr.lo, gr.hi);
     const int32_t tile0 = blockIdx.x * kTilesPerGroup + w * kTilesPerWave;
     uint32_t wave_gt = 0, gt = 0, mine = 0;  // lane u keeps the count of the wave's tile u
     int32_t tile_of_item = 0;
@@ -760,7 +742,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
                 if (lane == 0) base = atomicAdd(&st->gcount, static_cast<uint32_t>(__popcll(min_)));
                 base = __shfl(base, 0, LD_WAVE);
                 const uint32_t pos = base + mbcnt(min_);
-                if (in && pos < static_cast<uint32_t>(kGatherCap)) {
+                if (in && pos < gcap) {
                     gkey[pos] = key;
                     gtile[pos] = tile_of_item;
                 }
@@ -784,7 +766,9 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
 
 // One workgroup per segment: the exact threshold T and the number m of its ties to
 // keep, selected among the gathered keys; per-tile counts completed; group sums
-// scanned into output offsets.
+// scanned into output offsets. All gathered keys lie in one fine bin, so the radix
+// select runs on (key - first key of the bin): one 11-bit level per 11 bits of bin
+// width, and the digits spread over the histogram instead of piling on one counter.
 __global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
     __shared__ uint32_t lh[kBins];
     __shared__ uint32_t sh[kWaves];
@@ -793,43 +777,58 @@ __global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
     const GroupRange gr = seg_range(c, blockIdx.x);
     SegState* st = c.state + gr.seg;
     if (gr.k == 0 || gr.ngroup == 0 || st->mode != kModeCand) return;
-    const uint32_t krem1 = st->krem;
     const uint32_t ng = st->gcount;
-    const uint32_t* gkey = c.gkey + static_cast<int64_t>(gr.seg) * kGatherCap;
-    const int32_t* gtile = c.gtile + static_cast<int64_t>(gr.seg) * kGatherCap;
-    if (ng > static_cast<uint32_t>(kGatherCap)) {
+    const uint32_t* gkey = c.gkey + gather_first(gr.seg, gr.lo);
+    const int32_t* gtile = c.gtile + gather_first(gr.seg, gr.lo);
+    if (ng > gather_cap(gr.lo, gr.hi)) {
         mark_full(c, st, gr, &list0);  // too many keys share the threshold bin (massive ties)
         return;
     }
-    uint32_t key[kGatherItems];
-    uint32_t valid = 0;
-#pragma unroll
-    for (int i = 0; i < kGatherItems; ++i) {
-        const uint32_t p = i * kThreads + threadIdx.x;
-        key[i] = 0;
-        if (p < ng) {
-            key[i] = gkey[p];
-            valid |= 1u << i;
+    const uint32_t b1 = st->prefix, binsh = st->sh;
+    const uint32_t base = st->tau + (b1 << binsh);
+    const int bits = (b1 == static_cast<uint32_t>(kTopBin)) ? 31 : static_cast<int>(binsh);  // the top bin is open-ended
+    const int nlev = bits == 0 ? 1 : (bits + 10) / 11;
+    uint32_t prefix = 0, krem = st->krem;
+#pragma unroll 1
+    for (int lev = 0; lev < nlev; ++lev) {
+        const int shift = 11 * (nlev - 1 - lev);
+        for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+        __syncthreads();
+#pragma unroll 1
+        for (uint32_t p = threadIdx.x; p < ng; p += kThreads) {
+            const uint32_t rel = gkey[p] - base;
+            if (lev == 0 || ((rel ^ prefix) >> (shift + 11)) == 0) atomicAdd(&lh[(rel >> shift) & 0x7FFu], 1u);
         }
+        __syncthreads();
+        find_bin<kThreads, false>(lh, krem, sh, res);
+        prefix |= res[0] << shift;
+        krem = res[1];
+        __syncthreads();
     }
-    uint32_t m;
-    const uint32_t T = block_select<kThreads, kGatherItems>(key, valid, krem1, lh, sh, res, &m);
-#pragma unroll
-    for (int i = 0; i < kGatherItems; ++i) {
-        if (!((valid >> i) & 1u) || key[i] < T) continue;
-        const int32_t tile = gtile[i * kThreads + threadIdx.x];
-        if (key[i] > T) {
+    const uint32_t T = base + prefix, m = krem;
+    // The group sums are read back below by this same workgroup. The updates return their old
+    // value, so each has been performed when its result arrives; with the barrier that orders
+    // them before the reads. (A device-scope fence would do too, but it writes back the whole
+    // L2 and costs 30 us here.)
+    uint32_t seen = 0;
+#pragma unroll 1
+    for (uint32_t p = threadIdx.x; p < ng; p += kThreads) {
+        const uint32_t key = gkey[p];
+        if (key < T) continue;
+        const int32_t tile = gtile[p];
+        if (key > T) {
             atomicAdd(c.tile_gt + tile, 1u);
-            atomicAdd(c.group_gt + tile / kTilesPerGroup, 1u);
+            seen |= atomicAdd(c.group_gt + tile / kTilesPerGroup, 1u);
         } else {
             atomicAdd(c.tile_eq + tile, 1u);
-            atomicAdd(c.group_eq + tile / kTilesPerGroup, 1u);
+            seen |= atomicAdd(c.group_eq + tile / kTilesPerGroup, 1u);
         }
     }
-    __threadfence();
+    if (seen == 0xFFFFFFFFu) res[0] = seen;  // never true: keeps the results, and so the waits, alive
     __syncthreads();
     // exclusive scan over the segment's groups: records emitted / ties seen before each
     uint32_t carry_out = 0, carry_eq = 0;
+#pragma unroll 1
     for (int32_t q0 = 0; q0 < gr.ngroup; q0 += kThreads) {
         const int32_t q = q0 + threadIdx.x;
         uint32_t cg = 0, ce = 0;
@@ -1106,8 +1105,9 @@ Layout layout(int32_t n_seg, int64_t n_group) {
     L.tile_eq = take(4 * nt);
     L.group_gt = take(4 * ng);
     L.group_eq = take(4 * ng);
-    L.gkey = take(4 * ns * kGatherCap);
-    L.gtile = take(4 * ns * kGatherCap);
+    const size_t gather_entries = static_cast<size_t>(kGatherBase) * ns + nt * (kTile / kGatherPer) + 1;
+    L.gkey = take(4 * gather_entries);
+    L.gtile = take(4 * gather_entries);
     L.fail_groups = take(4 * ng);
     L.fail_count = take(4);
     L.total = o;
