@@ -556,17 +556,27 @@ __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __re
 }
 
 // ------------------------------------------------- passes over the candidates
-
-// A wave of a small pass owns kTilesPerWave consecutive tiles of its group. For
-// each live tile, in order: begin(u); then item(have, val, local, stored) for
-// batches of 64 candidates (one per lane, index order, called by all lanes
-// together; `local` is the element's offset inside the tile, `stored` tells that
-// the candidate comes from the slot); then end(u), u = 0.. being the tile's number
-// inside the wave. All slots of the wave are fetched before the first is used, so
-// that a wave waits for memory once. A tile whose slot overflowed is read back
-// from the residual (which then holds r + g unzeroed) and filtered with the same
-// test k_main applied.
+//
+// A wave of a small pass owns kTilesPerWave consecutive tiles of its group.
+//
+// Fast path, for tiles with at most kFast stored candidates (nearly all of them):
+// four tiles at a time, one per row of 16 lanes. A lane holds 8 consecutive
+// candidates of its row's tile (two 16-byte loads of values, one of in-tile
+// offsets), so one trip through the loop body serves four tiles, and per-tile sums
+// and prefixes are 16-lane row operations. These passes are bound by instruction
+// issue, not by memory: the body is kept small and rolled.
+//
+// Slow path (slow_tiles), for tiles with more stored candidates and for tiles whose
+// slot overflowed (read back from the residual, which then holds r + g unzeroed,
+// and filtered with the test k_main applied): begin(u); then item(have, val, local,
+// stored) for batches of 64 candidates (one per lane, index order, called by all
+// lanes together; `local` is the element's offset inside the tile, `stored` tells
+// that the candidate comes from the slot); then end(u).
 constexpr int kTilesPerWave = kTilesPerGroup / kWaves;
+constexpr int kRow = 16;                      // lanes per tile in the fast path
+constexpr int kPerLane = 8;                   // candidates per lane
+constexpr uint32_t kFast = kRow * kPerLane;   // 128
+constexpr int kQuads = kTilesPerWave / 4;
 
 // Lane u < kTilesPerWave: the candidate count of the wave's tile u (k_main writes a
 // count for every tile slot of every group, 0 past the end of a segment). Fetched
@@ -577,38 +587,66 @@ __device__ __forceinline__ uint32_t wave_counts(const Ctx& c, int32_t group) {
     return lane < kTilesPerWave ? c.cnt[tile0 + lane] : 0u;
 }
 
+__device__ __forceinline__ uint32_t row_iscan(uint32_t x) {  // inclusive scan over a row of 16 lanes
+#pragma unroll
+    for (int d = 1; d < kRow; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d, kRow);
+        if ((ld_lane() & (kRow - 1)) >= d) x += y;
+    }
+    return x;
+}
+
+__device__ __forceinline__ uint32_t row_sum(uint32_t x) {
+#pragma unroll
+    for (int d = kRow / 2; d > 0; d >>= 1) x += __shfl_xor(x, d, kRow);
+    return x;
+}
+
+struct Quad {
+    float v[kPerLane];      // candidate values (entries at or past `have` are stale)
+    uint32_t x[kPerLane];   // their offsets inside the tile (IDX only)
+    uint32_t have;          // valid entries of this lane: 0..kPerLane
+    uint32_t cn;            // stored count of the row's tile (kOverflow, or > kFast: not served here)
+    int u;                  // the row's tile, counted inside the wave
+};
+
+// Fetches the lane's part of quad q (tiles 4q .. 4q+3 of the wave); q >= kQuads fetches nothing.
+template <bool IDX>
+__device__ __forceinline__ void quad_fetch(const Ctx& c, int32_t tile0, uint32_t mycnt, int q, Quad& Q) {
+    const int lane = ld_lane();
+    const int u = 4 * (q < kQuads ? q : 0) + (lane >> 4);
+    const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
+    const uint32_t n = (q < kQuads && cn <= kFast) ? cn : 0u;
+    const uint32_t first = static_cast<uint32_t>(lane & (kRow - 1)) * kPerLane;
+    const int64_t at = static_cast<int64_t>(tile0 + u) * kSlot + first;
+    ld_f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
+    ld_u32x4 xi = {0u, 0u, 0u, 0u};
+    if (first < n) a = *reinterpret_cast<const ld_f32x4*>(c.cval + at);
+    if (first + 4 < n) b = *reinterpret_cast<const ld_f32x4*>(c.cval + at + 4);
+    if (IDX && first < n) xi = *reinterpret_cast<const ld_u32x4*>(c.cidx + at);
+    Q.v[0] = a.x; Q.v[1] = a.y; Q.v[2] = a.z; Q.v[3] = a.w;
+    Q.v[4] = b.x; Q.v[5] = b.y; Q.v[6] = b.z; Q.v[7] = b.w;
+    const uint32_t xw[4] = {xi.x, xi.y, xi.z, xi.w};
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) Q.x[j] = (j & 1) ? (xw[j >> 1] >> 16) : (xw[j >> 1] & 0xFFFFu);
+    Q.have = first < n ? umin(n - first, static_cast<uint32_t>(kPerLane)) : 0u;
+    Q.cn = cn;
+    Q.u = u;
+}
+
 template <bool IDX, class Begin, class Item, class End>
-__device__ __forceinline__ void wave_tiles(const Ctx& c, const float* __restrict__ r, const GroupRange& gr,
+__device__ __forceinline__ void slow_tiles(const Ctx& c, const float* __restrict__ r, const GroupRange& gr,
                                            int32_t group, uint32_t mycnt, uint32_t tau, Begin&& begin, Item&& item,
                                            End&& end) {
     const int lane = ld_lane();
-    const int w = threadIdx.x >> 6;
-    const int tl0 = w * kTilesPerWave;
+    const int tl0 = static_cast<int>(threadIdx.x >> 6) * kTilesPerWave;
     const int32_t tile0 = group * kTilesPerGroup + tl0;
     const int64_t tbase0 = gr.base + static_cast<int64_t>(tl0) * kTile;
-    int live = 0;
-    if (tbase0 < gr.hi) {
-        const int64_t nt = (gr.hi - tbase0 + kTile - 1) / kTile;
-        live = nt < kTilesPerWave ? static_cast<int>(nt) : kTilesPerWave;
-    }
-    // rolled loop, the next tile's slot fetched while the current one is worked on: the loop body is
-    // the whole code of the pass (a fully unrolled version spends its time fetching instructions)
-    auto fetch = [&](int u, float& a0, float& a1, uint32_t& b0, uint32_t& b1) {
-        const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u < kTilesPerWave ? u : 0, LD_WAVE));
-        const uint32_t n = (u >= live || cn == kOverflow) ? 0u : cn;
-        const int64_t slot = static_cast<int64_t>(tile0 + u) * kSlot;
-        const bool h0 = static_cast<uint32_t>(lane) < n, h1 = static_cast<uint32_t>(lane + LD_WAVE) < n;
-        a0 = h0 ? c.cval[slot + lane] : 0.0f;
-        a1 = h1 ? c.cval[slot + LD_WAVE + lane] : 0.0f;
-        b0 = (IDX && h0) ? c.cidx[slot + lane] : 0u;
-        b1 = (IDX && h1) ? c.cidx[slot + LD_WAVE + lane] : 0u;
-    };
-    float v0, v1, nv0, nv1;
-    uint32_t x0, x1, nx0, nx1;
-    fetch(0, v0, v1, x0, x1);
-#pragma unroll 1
-    for (int u = 0; u < live; ++u) {
-        fetch(u + 1, nv0, nv1, nx0, nx1);
+    // tiles of the wave that are not served by the fast path
+    uint64_t todo = __ballot(lane < kTilesPerWave && mycnt > kFast);
+    while (todo) {
+        const int u = __builtin_ctzll(todo);
+        todo &= todo - 1;
         const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
         const bool stored = cn != kOverflow;
         const uint32_t total = stored ? cn : static_cast<uint32_t>(kTile);
@@ -620,26 +658,19 @@ __device__ __forceinline__ void wave_tiles(const Ctx& c, const float* __restrict
             bool have = b0 + lane < total;
             float v;
             uint32_t x;
-            if (!stored) {
+            if (stored) {
+                v = have ? c.cval[slot + b0 + lane] : 0.0f;
+                x = (IDX && have) ? c.cidx[slot + b0 + lane] : 0u;
+            } else {
                 const int64_t e = tbase + b0 + lane;
                 const bool in = e >= gr.lo && e < gr.hi;
                 v = in ? r[e] : 0.0f;
                 x = b0 + lane;
                 have = in && ld_key(v) >= tau;
-            } else if (b0 == 0) {
-                v = v0;
-                x = x0;
-            } else if (b0 == LD_WAVE) {
-                v = v1;
-                x = x1;
-            } else {
-                v = have ? c.cval[slot + b0 + lane] : 0.0f;
-                x = (IDX && have) ? c.cidx[slot + b0 + lane] : 0u;
             }
             item(have, v, x, stored);
         }
         end(u);
-        v0 = nv0; v1 = nv1; x0 = nx0; x1 = nx1;
     }
 }
 
@@ -675,9 +706,20 @@ __global__ __launch_bounds__(kThreads) void k_hist(const float* __restrict__ r, 
     const GroupRange gr = group_range(c, blockIdx.x);
     if (gr.k == 0) return;
     const uint32_t tau = gr.tau, binsh = gr.sh;
+    const int32_t tile0 = blockIdx.x * kTilesPerGroup + static_cast<int>(threadIdx.x >> 6) * kTilesPerWave;
     for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
     __syncthreads();
-    wave_tiles<false>(
+    Quad Q, N;
+    quad_fetch<false>(c, tile0, mycnt, 0, Q);
+#pragma unroll 1
+    for (int q = 0; q < kQuads; ++q) {
+        quad_fetch<false>(c, tile0, mycnt, q + 1, N);
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j)
+            if (static_cast<uint32_t>(j) < Q.have) atomicAdd(&lh[fine_bin(ld_key(Q.v[j]), tau, binsh)], 1u);
+        Q = N;
+    }
+    slow_tiles<false>(
         c, r, gr, blockIdx.x, mycnt, tau, [](int) {},
         [&](bool have, float v, uint32_t, bool) {
             if (have) atomicAdd(&lh[fine_bin(ld_key(v), tau, binsh)], 1u);
@@ -723,9 +765,43 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     int32_t* gtile = c.gtile + gather_first(gr.seg, gr.lo);
     const uint32_t gcap = gather_cap(gr.lo, gr.hi);
     const int32_t tile0 = blockIdx.x * kTilesPerGroup + w * kTilesPerWave;
-    uint32_t wave_gt = 0, gt = 0, mine = 0;  // lane u keeps the count of the wave's tile u
+    uint32_t part_gt = 0;  // fast path: the first lane of a row sums the row's tiles
+    Quad Q, N;
+    quad_fetch<false>(c, tile0, mycnt, 0, Q);
+#pragma unroll 1
+    for (int q = 0; q < kQuads; ++q) {
+        quad_fetch<false>(c, tile0, mycnt, q + 1, N);
+        uint32_t cnt = 0, in = 0;
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            const uint32_t bin = fine_bin(ld_key(Q.v[j]), tau, binsh);
+            const bool valid = static_cast<uint32_t>(j) < Q.have;
+            cnt += valid && bin > b1;
+            in |= static_cast<uint32_t>(valid && bin == b1) << j;
+        }
+        if (__ballot(in != 0)) {  // a few keys per segment only
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) {
+                if ((in >> j) & 1u) {
+                    const uint32_t pos = atomicAdd(&st->gcount, 1u);
+                    if (pos < gcap) {
+                        gkey[pos] = ld_key(Q.v[j]);
+                        gtile[pos] = tile0 + Q.u;
+                    }
+                }
+            }
+        }
+        cnt = row_sum(cnt);
+        if ((lane & (kRow - 1)) == 0 && Q.cn <= kFast) {
+            c.tile_gt[tile0 + Q.u] = cnt;
+            c.tile_eq[tile0 + Q.u] = 0;
+            part_gt += cnt;
+        }
+        Q = N;
+    }
+    uint32_t slow_gt = 0, gt = 0;
     int32_t tile_of_item = 0;
-    wave_tiles<false>(
+    slow_tiles<false>(
         c, r, gr, blockIdx.x, mycnt, tau,
         [&](int u) {
             gt = 0;
@@ -749,13 +825,13 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
             }
         },
         [&](int u) {
-            if (lane == u) mine = gt;
-            wave_gt += gt;
+            if (lane == 0) {
+                c.tile_gt[tile0 + u] = gt;
+                c.tile_eq[tile0 + u] = 0;
+            }
+            slow_gt += gt;
         });
-    if (lane < kTilesPerWave) {
-        c.tile_gt[tile0 + lane] = mine;
-        c.tile_eq[tile0 + lane] = 0;
-    }
+    const uint32_t wave_gt = ld_wave_sum(part_gt) + slow_gt;
     if (lane == 0) wsum[w] = wave_gt;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -865,9 +941,21 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
     const int tl0 = w * kTilesPerWave;
+    const int32_t tile0 = blockIdx.x * kTilesPerGroup + tl0;
     int64_t tbase = 0;
+    Quad Q, N;
     if (st->mode != kModeCand) {
-        wave_tiles<true>(
+        quad_fetch<true>(c, tile0, mycnt, 0, Q);
+#pragma unroll 1
+        for (int q = 0; q < kQuads; ++q) {
+            quad_fetch<true>(c, tile0, mycnt, q + 1, N);
+            float* rt = r + gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile;
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j)
+                if (static_cast<uint32_t>(j) < Q.have && ld_key(Q.v[j]) >= test) rt[Q.x[j]] = Q.v[j];
+            Q = N;
+        }
+        slow_tiles<true>(
             c, r, gr, blockIdx.x, mycnt, tau,
             [&](int u) { tbase = gr.base + static_cast<int64_t>(tl0 + u) * kTile; },
             [&](bool have, float v, uint32_t local, bool stored) {
@@ -886,9 +974,45 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
         tile_eqb[lane] = eq_before;
     }
     __syncthreads();
+    quad_fetch<true>(c, tile0, mycnt, 0, Q);
+#pragma unroll 1
+    for (int q = 0; q < kQuads; ++q) {
+        quad_fetch<true>(c, tile0, mycnt, q + 1, N);
+        const uint32_t out_tile = tile_out[tl0 + Q.u], eq_tile = tile_eqb[tl0 + Q.u];
+        uint32_t gtm = 0, eqm = 0;
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            const uint32_t key = ld_key(Q.v[j]);
+            const bool valid = static_cast<uint32_t>(j) < Q.have;
+            gtm |= static_cast<uint32_t>(valid && key > T) << j;
+            eqm |= static_cast<uint32_t>(valid && key == T) << j;
+        }
+        const uint32_t mine = __popc(gtm) | (__popc(eqm) << 16);  // a tile holds at most 128 here
+        const uint32_t before = row_iscan(mine) - mine;
+        uint32_t gt_before = before & 0xFFFFu;
+        uint32_t eq_rank = eq_tile + (before >> 16);
+        float* rt = r + gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile;
+        const int64_t e0 = gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile;
+        const int64_t o0 = gr.out0 + out_tile;
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            const bool is_gt = (gtm >> j) & 1u, is_eq = (eqm >> j) & 1u;
+            const bool selected = is_gt || (is_eq && eq_rank < m);
+            if (selected) {
+                const int64_t pos = o0 + gt_before + (umin(eq_rank, m) - umin(eq_tile, m));
+                out_idx[pos] = static_cast<int32_t>(e0 + Q.x[j]);
+                out_val[pos] = Q.v[j];
+            }
+            const bool zeroed = ld_key(Q.v[j]) >= test;
+            if (static_cast<uint32_t>(j) < Q.have && selected != zeroed) rt[Q.x[j]] = selected ? 0.0f : Q.v[j];
+            gt_before += is_gt;
+            eq_rank += is_eq;
+        }
+        Q = N;
+    }
     uint32_t run_out = 0;  // records of the segment emitted before this point
     uint32_t run_eq = 0;   // ties seen before this point
-    wave_tiles<true>(
+    slow_tiles<true>(
         c, r, gr, blockIdx.x, mycnt, tau,
         [&](int u) {
             run_out = tile_out[tl0 + u];
