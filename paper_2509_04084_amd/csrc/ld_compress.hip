@@ -933,6 +933,8 @@ __global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
 __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_t* __restrict__ out_idx,
                                                    float* __restrict__ out_val, Ctx c) {
     __shared__ uint32_t tile_out[kTilesPerGroup], tile_eqb[kTilesPerGroup];
+    __shared__ int32_t stage_i[kWaves][4 * kFast];
+    __shared__ float stage_v[kWaves][4 * kFast];
     const uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
     const SegState* st = c.state + gr.seg;
@@ -992,22 +994,39 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
         uint32_t gt_before = before & 0xFFFFu;
         uint32_t eq_rank = eq_tile + (before >> 16);
         float* rt = r + gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile;
-        const int64_t e0 = gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile;
-        const int64_t o0 = gr.out0 + out_tile;
+        const int32_t e0 = static_cast<int32_t>(gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile);
+        // the records of a row's tile are staged in LDS at their rank inside the tile and then
+        // written out as contiguous runs (stores of single records from scattered lanes cost
+        // three times as much)
+        int32_t* si = stage_i[w] + (lane >> 4) * kFast;
+        float* sv = stage_v[w] + (lane >> 4) * kFast;
+        uint32_t rank = 0;
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
             const bool is_gt = (gtm >> j) & 1u, is_eq = (eqm >> j) & 1u;
             const bool selected = is_gt || (is_eq && eq_rank < m);
+            rank = gt_before + (umin(eq_rank, m) - umin(eq_tile, m));
             if (selected) {
-                const int64_t pos = o0 + gt_before + (umin(eq_rank, m) - umin(eq_tile, m));
-                out_idx[pos] = static_cast<int32_t>(e0 + Q.x[j]);
-                out_val[pos] = Q.v[j];
+                si[rank] = e0 + static_cast<int32_t>(Q.x[j]);
+                sv[rank] = Q.v[j];
             }
             const bool zeroed = ld_key(Q.v[j]) >= test;
             if (static_cast<uint32_t>(j) < Q.have && selected != zeroed) rt[Q.x[j]] = selected ? 0.0f : Q.v[j];
             gt_before += is_gt;
             eq_rank += is_eq;
         }
+        rank = gt_before + (umin(eq_rank, m) - umin(eq_tile, m));  // in a row's last lane: records of the tile
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            const uint32_t cnt = static_cast<uint32_t>(__shfl(static_cast<int>(rank), row * kRow + kRow - 1, LD_WAVE));
+            const int64_t o0 = gr.out0 + tile_out[tl0 + 4 * q + row];
+            for (uint32_t i = lane; i < cnt; i += LD_WAVE) {
+                out_idx[o0 + i] = stage_i[w][row * kFast + i];
+                out_val[o0 + i] = stage_v[w][row * kFast + i];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         Q = N;
     }
     uint32_t run_out = 0;  // records of the segment emitted before this point
