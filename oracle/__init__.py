@@ -14,6 +14,9 @@ Functions (all operate on host memory, single threaded):
 * ``snapshot(src)`` - bit copy of a bf16 layer (Snapshot of Algorithm 2).
 * ``adam_replay(w, m, v, grads, step0, lr, beta1, beta2, eps)`` - dense Adam
   merge (Algorithm 2 "Merge in CPU", Eq. (4)).
+* ``sparse_adam_replay(w, m, v, idx_list, val_list, step0, lr, beta1, beta2, eps)``
+  - sparse diffs replayed through Adam (Recovery of Algorithm 1 with the update
+  the paper names there).
 """
 from __future__ import annotations
 
@@ -58,6 +61,10 @@ def _load():
                                            ctypes.c_int64, ctypes.c_float, ctypes.c_float,
                                            ctypes.c_float, ctypes.c_float]
         lib.oracle_adam_replay.restype = None
+        lib.oracle_sparse_adam_replay.argtypes = [p, p, p, ctypes.c_int64, p, p, p, ctypes.c_int32,
+                                                  ctypes.c_int64, ctypes.c_float, ctypes.c_float,
+                                                  ctypes.c_float, ctypes.c_float]
+        lib.oracle_sparse_adam_replay.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -137,4 +144,30 @@ def adam_replay(w, m, v, grads, step0: int, lr: float, beta1: float, beta2: floa
     _load().oracle_adam_replay(_ptr(w2), _ptr(m2), _ptr(v2), w2.shape[0], gp, W, int(step0),
                                ctypes.c_float(lr), ctypes.c_float(beta1),
                                ctypes.c_float(beta2), ctypes.c_float(eps))
+    return w2, m2, v2
+
+
+def sparse_adam_replay(w, m, v, idx_list, val_list, step0: int, lr: float, beta1: float, beta2: float,
+                       eps: float):
+    """Replays sparse diffs as Adam steps step0+1..step0+W (gradient zero off the records).
+
+    Returns new (w, m, v) float32 arrays; inputs are not modified.
+    """
+    w2 = np.array(w, dtype=np.float32, copy=True, order="C")
+    m2 = np.array(m, dtype=np.float32, copy=True, order="C")
+    v2 = np.array(v, dtype=np.float32, copy=True, order="C")
+    W = len(idx_list)
+    assert len(val_list) == W
+    idxs = [_c(a, np.int32) for a in idx_list]
+    vals = [_c(a, np.float32) for a in val_list]
+    K = np.array([a.shape[0] for a in idxs], dtype=np.int64)
+    for a, b in zip(idxs, vals):
+        assert a.shape == b.shape
+    ip = (ctypes.c_void_p * max(W, 1))(*[a.ctypes.data for a in idxs])
+    vp = (ctypes.c_void_p * max(W, 1))(*[a.ctypes.data for a in vals])
+    rc = _load().oracle_sparse_adam_replay(_ptr(w2), _ptr(m2), _ptr(v2), w2.shape[0], ip, vp, _ptr(K), W,
+                                           int(step0), ctypes.c_float(lr), ctypes.c_float(beta1),
+                                           ctypes.c_float(beta2), ctypes.c_float(eps))
+    if rc != 0:
+        raise ValueError("oracle_sparse_adam_replay: index out of range")
     return w2, m2, v2

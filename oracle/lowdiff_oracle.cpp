@@ -25,6 +25,9 @@
 //   oracle_snapshot : Snapshot(G^n_t) of Algorithm 2 - a bit copy of one layer.
 //   oracle_adam_replay : "Merge in CPU" of Algorithm 2, M <- M + Adam(o_t, G_t)
 //       (Eq. (4)), with the textbook bias-corrected Adam of Kingma & Ba.
+//   oracle_sparse_adam_replay : the Recovery loop of Algorithm 1 with the update
+//       the paper itself names there (decompress, then Adam on model and optimizer
+//       state), for diffs that are sparse.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -164,6 +167,42 @@ void oracle_adam_replay(float* w, float* m, float* v, int64_t n, const uint16_t*
             w[i] = static_cast<float>(static_cast<double>(w[i]) - lrd * mhat / (std::sqrt(vhat) + epsd));
         }
     }
+}
+
+// Replay W sparse diffs through Adam onto fp32 (w, m, v): the recovery loop of
+// Algorithm 1 as the paper states it, M_{j+1} = M_j + Adam(G_j), where G_j is the
+// decompressed diff j - a dense gradient that is val at the recorded positions and
+// zero everywhere else.  Every element takes every step (a zero gradient still
+// decays m and v and moves w while m is non-zero).  Steps step0+1 .. step0+W;
+// arithmetic as in oracle_adam_replay.  Returns 0, or -1 on an index out of range.
+int oracle_sparse_adam_replay(float* w, float* m, float* v, int64_t n, const int32_t* const* idx,
+                              const float* const* val, const int64_t* K, int32_t W, int64_t step0,
+                              float lr, float beta1, float beta2, float eps) {
+    const double b1 = beta1, b2 = beta2, lrd = lr, epsd = eps;
+    std::vector<float> g(static_cast<size_t>(n));
+    for (int32_t t = 0; t < W; ++t) {
+        // Comp^-1: decompress diff t into a dense gradient
+        std::fill(g.begin(), g.end(), 0.0f);
+        for (int64_t j = 0; j < K[t]; ++j) {
+            const int64_t i = idx[t][j];
+            if (i < 0 || i >= n) return -1;
+            g[static_cast<size_t>(i)] = val[t][j];
+        }
+        const double s = static_cast<double>(step0 + 1 + t);
+        const double bc1 = 1.0 - std::pow(b1, s);
+        const double bc2 = 1.0 - std::pow(b2, s);
+        for (int64_t i = 0; i < n; ++i) {
+            const double gi = g[static_cast<size_t>(i)];
+            const float mf = static_cast<float>(b1 * m[i] + (1.0 - b1) * gi);
+            const float vf = static_cast<float>(b2 * v[i] + (1.0 - b2) * gi * gi);
+            m[i] = mf;
+            v[i] = vf;
+            const double mhat = static_cast<double>(mf) / bc1;
+            const double vhat = static_cast<double>(vf) / bc2;
+            w[i] = static_cast<float>(static_cast<double>(w[i]) - lrd * mhat / (std::sqrt(vhat) + epsd));
+        }
+    }
+    return 0;
 }
 
 }  // extern "C"

@@ -461,3 +461,105 @@ def test_bf16_widening_matches_torch():
     _, m, _ = oracle.adam_replay(z, z, z, [hb], 0, 0.0, 0.0, 0.0, 1.0)
     want = torch.from_numpy(hb.view(np.int16)).view(torch.bfloat16).float().numpy()
     assert_bits_equal(m, want)
+
+
+# ------------------------------------------------------- sparse diffs through Adam
+
+def _sparse_window(n, W, dens, rs, scale=1e-3):
+    idxs, vals = [], []
+    for _ in range(W):
+        kk = max(1, int(round(n * dens)))
+        idxs.append(np.sort(rs.choice(n, kk, replace=False)).astype(np.int32))
+        vals.append((rs.standard_normal(kk) * scale).astype(np.float32))
+    return idxs, vals
+
+
+def test_sparse_adam_matches_torch_optimizer_on_densified_gradients():
+    # library pin: torch.optim.Adam fed the decompressed (dense, mostly zero) gradients
+    n, W, step0 = 3000, 6, 4
+    rs = np.random.RandomState(31)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    m0 = (rs.standard_normal(n) * 1e-4).astype(np.float32)
+    v0 = (rs.standard_normal(n) ** 2 * 1e-7).astype(np.float32)
+    idxs, vals = _sparse_window(n, W, 0.05, rs)
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8)
+    p = torch.nn.Parameter(torch.tensor(w0, dtype=torch.float64))
+    opt = torch.optim.Adam([p], lr=hp["lr"], betas=(float(np.float32(0.9)), float(np.float32(0.999))),
+                           eps=hp["eps"], weight_decay=0, amsgrad=False)
+    p.grad = torch.zeros_like(p)
+    opt.step()
+    st = opt.state[p]
+    st["step"].fill_(step0)
+    st["exp_avg"].copy_(torch.tensor(m0, dtype=torch.float64))
+    st["exp_avg_sq"].copy_(torch.tensor(v0, dtype=torch.float64))
+    with torch.no_grad():
+        p.copy_(torch.tensor(w0, dtype=torch.float64))
+    for i, v in zip(idxs, vals):
+        g = torch.zeros(n, dtype=torch.float64)
+        g[torch.from_numpy(i.astype(np.int64))] = torch.from_numpy(v.astype(np.float64))
+        p.grad = g
+        opt.step()
+    w, m, v = oracle.sparse_adam_replay(w0, m0, v0, idxs, vals, step0, **hp)
+    np.testing.assert_allclose(w, p.detach().numpy(), rtol=1e-6, atol=1e-9)
+    np.testing.assert_allclose(m, st["exp_avg"].numpy(), rtol=1e-6, atol=1e-10)
+    np.testing.assert_allclose(v, st["exp_avg_sq"].numpy(), rtol=1e-6, atol=1e-15)
+
+
+def test_sparse_adam_equals_dense_replay_when_every_position_is_recorded():
+    # a diff that records all n positions (bf16-representable values) is a dense gradient
+    n, W = 2000, 3
+    rs = np.random.RandomState(32)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    z = np.zeros(n, np.float32)
+    gb = [_bf16_bits(rs.standard_normal(n) * 1e-3) for _ in range(W)]
+    gf = [torch.from_numpy(b.view(np.int16)).view(torch.bfloat16).float().numpy() for b in gb]
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8)
+    dense = oracle.adam_replay(w0, z, z, gb, 0, **hp)
+    allidx = np.arange(n, dtype=np.int32)
+    sparse = oracle.sparse_adam_replay(w0, z, z, [allidx] * W, gf, 0, **hp)
+    for a, b in zip(dense, sparse):
+        assert_bits_equal(a, b)
+
+
+def test_sparse_adam_zero_gradient_positions_and_window_semantics():
+    n, W = 1500, 5
+    rs = np.random.RandomState(33)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    m0 = (rs.standard_normal(n) * 1e-4).astype(np.float32)
+    v0 = (rs.standard_normal(n) ** 2 * 1e-7 + 1e-12).astype(np.float32)
+    idxs, vals = _sparse_window(n, W, 0.02, rs)
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8)
+    w, m, v = oracle.sparse_adam_replay(w0, m0, v0, idxs, vals, 2, **hp)
+    untouched = np.ones(n, bool)
+    for i in idxs:
+        untouched[i] = False
+    assert untouched.sum() > n // 2
+    # never-recorded positions: m and v decay geometrically; w still moves while m != 0
+    np.testing.assert_allclose(m[untouched], m0[untouched].astype(np.float64) * np.float64(np.float32(0.9)) ** W,
+                               rtol=1e-6)
+    np.testing.assert_allclose(v[untouched], v0[untouched].astype(np.float64) * np.float64(np.float32(0.999)) ** W,
+                               rtol=1e-6)
+    assert np.all(w[untouched] != w0[untouched])
+    # closed form for an untouched element: w_T = w_0 - sum_s lr * (b1^j m0 / bc1_s) / (sqrt(b2^j v0 / bc2_s) + eps)
+    b1, b2 = np.float64(np.float32(0.9)), np.float64(np.float32(0.999))
+    want = w0.astype(np.float64).copy()
+    for j in range(1, W + 1):
+        s = 2 + j
+        want -= np.float64(np.float32(1e-3)) * (b1 ** j * m0 / (1 - b1 ** s)) / (np.sqrt(b2 ** j * v0 / (1 - b2 ** s)) + 1e-8)
+    np.testing.assert_allclose(w[untouched], want[untouched], rtol=2e-6, atol=1e-8)
+    # zero state and never recorded: nothing changes at all
+    z = np.zeros(n, np.float32)
+    w2, m2, v2 = oracle.sparse_adam_replay(w0, z, z, idxs, vals, 0, **hp)
+    assert_bits_equal(w2[untouched], w0[untouched])
+    assert_bits_equal(m2[untouched], z[untouched])
+    assert_bits_equal(v2[untouched], z[untouched])
+    # a window in one call == one call per diff, bit for bit (state round-trips through fp32)
+    a, b, c = w0, m0, v0
+    for t in range(W):
+        a, b, c = oracle.sparse_adam_replay(a, b, c, [idxs[t]], [vals[t]], 2 + t, **hp)
+    for x, y in zip((w, m, v), (a, b, c)):
+        assert_bits_equal(x, y)
+    # first step from zero state at a recorded position: delta w = -lr * g / (|g| + eps)
+    w3, _, _ = oracle.sparse_adam_replay(w0, z, z, [idxs[0]], [vals[0]], 0, **hp)
+    g = vals[0].astype(np.float64)
+    np.testing.assert_allclose(w3[idxs[0]], w0[idxs[0]] - 1e-3 * g / (np.abs(g) + 1e-8), rtol=1e-6, atol=1e-9)
