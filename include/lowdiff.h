@@ -3,7 +3,7 @@
  *
  * The library turns each training iteration's gradient into a differential
  * checkpoint and merges a window of such differentials onto a dense base
- * checkpoint.  Four operations, all executed by hand-written HIP kernels:
+ * checkpoint.  Five operations, all executed by hand-written HIP kernels:
  *
  *   ld_compress_topk     Comp of Algorithm 1 (Sec. IV-B): the compressed
  *                        gradient that LowDiff reuses as the differential
@@ -18,6 +18,9 @@
  *   ld_merge_dense_adam  "Merge in CPU" of Algorithm 2, M <- M + Adam(o_t, G_t)
  *                        (Eq. (4)): incremental merge of dense diffs into the
  *                        resident replica (kept in HBM here).
+ *   ld_merge_sparse_adam Recovery loop of Algorithm 1 with the paper's own update:
+ *                        sparse diffs decompressed and merged through Adam into
+ *                        model and optimizer state.
  *
  * General conventions
  *   - Pointers marked "dev" are device (HBM) addresses of the current HIP
@@ -191,6 +194,35 @@ ld_status ld_merge_sparse_strategy(float* w, int64_t n,
 ld_status ld_merge_dense_adam(float* w, float* m, float* v, int64_t n,
                               const void* const* grads_bf16, int32_t W, int64_t step0,
                               float lr, float beta1, float beta2, float eps, ld_stream stream);
+
+/* ------------------------------------------------------------------------
+ * ld_merge_sparse_adam - replay a window of W sparse diffs through Adam onto
+ * (w, m, v): the Recovery loop of Algorithm 1 (Sec. IV-B) with the update the
+ * paper names there - decompress diff j (Comp^-1), then M_{j+1} = M_j + Adam(G_j)
+ * (Eq. (4)) on the model and the optimizer state.  For t = 0..W-1, step
+ * s = step0+1+t, with g_i = val[t][j] where idx[t][j] = i and g_i = 0 elsewhere:
+ *   m <- beta1*m + (1-beta1)*g
+ *   v <- beta2*v + (1-beta2)*g*g
+ *   w <- w - lr * (m / (1-beta1^s)) / (sqrt(v / (1-beta2^s)) + eps)
+ * for EVERY element i (a zero gradient still decays m and v and moves w), in
+ * fp32, the same arithmetic as ld_merge_dense_adam.  One call with W diffs gives
+ * bit for bit the result of W calls with one diff each.
+ *
+ *   w, m, v    dev  [n] fp32 in/out, n <= 2^31-1
+ *   idx, val   host arrays of W dev pointers; idx[t] int32[K[t]] strictly
+ *              ascending and in [0, n); val[t] fp32[K[t]]
+ *   K          host [W] int64, 0 <= K[t] <= n
+ *   W          0 <= W <= LD_MAX_WINDOW (0 enqueues nothing)
+ *   step0      >= 0, optimizer steps already contained in (w, m, v)
+ *   workspace  dev, 256-byte aligned, ld_merge_sparse_adam_workspace() bytes
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_WORKSPACE, LD_ERR_HIP.
+ */
+size_t    ld_merge_sparse_adam_workspace(int64_t n, int32_t W, const int64_t* K /* host */);
+ld_status ld_merge_sparse_adam(float* w, float* m, float* v, int64_t n,
+                               const int32_t* const* idx, const float* const* val,
+                               const int64_t* K, int32_t W, int64_t step0,
+                               float lr, float beta1, float beta2, float eps,
+                               void* workspace, size_t workspace_bytes, ld_stream stream);
 
 #ifdef __cplusplus
 }

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "lowdiff.h"
@@ -24,6 +25,35 @@ static inline bool ld_aligned(const void* p, size_t a) {
 }
 
 static inline size_t ld_round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Per-step scalars of an Adam replay window, prepared on the host in double.
+#define LD_MAX_ADAM_STEPS 64
+struct LdAdamSteps {
+    float lr_over_bc1[LD_MAX_ADAM_STEPS];  // lr / (1 - beta1^s)
+    float inv_bc2[LD_MAX_ADAM_STEPS];      // 1 / (1 - beta2^s)
+    float beta1, one_m_beta1, beta2, one_m_beta2, eps;
+};
+
+// Scalars of steps step0+1 .. step0+W (W <= LD_MAX_ADAM_STEPS).
+static inline void ld_fill_adam_steps(LdAdamSteps& a, int32_t W, int64_t step0, float lr, float beta1,
+                                      float beta2, float eps) {
+    for (int32_t t = 0; t < LD_MAX_ADAM_STEPS; ++t) {
+        a.lr_over_bc1[t] = 0.0f;
+        a.inv_bc2[t] = 0.0f;
+    }
+    for (int32_t t = 0; t < W; ++t) {
+        const double s = static_cast<double>(step0 + 1 + t);
+        const double bc1 = 1.0 - pow(static_cast<double>(beta1), s);
+        const double bc2 = 1.0 - pow(static_cast<double>(beta2), s);
+        a.lr_over_bc1[t] = static_cast<float>(static_cast<double>(lr) / bc1);
+        a.inv_bc2[t] = static_cast<float>(1.0 / bc2);
+    }
+    a.beta1 = beta1;
+    a.one_m_beta1 = 1.0f - beta1;
+    a.beta2 = beta2;
+    a.one_m_beta2 = 1.0f - beta2;
+    a.eps = eps;
+}
 
 #ifdef __HIPCC__
 
@@ -73,6 +103,22 @@ __device__ __forceinline__ uint32_t ld_block_escan256(uint32_t x, uint32_t* sh, 
     if (w > 2) base += t2;
     __syncthreads();
     return base + inc - x;
+}
+
+__device__ __forceinline__ float ld_bf16_widen(uint32_t h) { return __uint_as_float(h << 16); }
+
+// One Adam step on one element (Eq. (4); bias-corrected, eps added to the root of the
+// corrected second moment). The only place the arithmetic is written: every replay
+// kernel, fused window or single step, dense or sparse gradient, runs these operations.
+//   lr_bc1 = lr / (1 - beta1^s), ibc2 = 1 / (1 - beta2^s), both prepared on the host in double
+__device__ __forceinline__ void ld_adam_step(float& w, float& m, float& v, float g, float b1,
+                                             float omb1, float b2, float omb2, float eps,
+                                             float lr_bc1, float ibc2) {
+    m = __fmaf_rn(b1, m, __fmul_rn(omb1, g));
+    v = __fmaf_rn(b2, v, __fmul_rn(__fmul_rn(omb2, g), g));
+    const float denom = __fadd_rn(__builtin_amdgcn_sqrtf(__fmul_rn(v, ibc2)), eps);
+    const float upd = __fmul_rn(__fmul_rn(lr_bc1, m), __builtin_amdgcn_rcpf(denom));
+    w = __fsub_rn(w, upd);
 }
 
 // Device-scope load that is not served from a stale per-CU cache line.

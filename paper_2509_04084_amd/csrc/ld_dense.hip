@@ -83,25 +83,9 @@ __global__ __launch_bounds__(kCopyThreads) void k_snapshot_batch(CopyBatch cb) {
 
 struct AdamArgs {
     const uint16_t* grad[LD_MAX_ADAM_WINDOW];
-    float lr_over_bc1[LD_MAX_ADAM_WINDOW];  // lr / (1 - beta1^s)
-    float inv_bc2[LD_MAX_ADAM_WINDOW];      // 1 / (1 - beta2^s)
-    float beta1, one_m_beta1, beta2, one_m_beta2, eps;
+    LdAdamSteps s;
     int32_t W;
 };
-
-__device__ __forceinline__ float bf16_widen(uint32_t h) { return __uint_as_float(h << 16); }
-
-// One Adam step on one element; the only place the arithmetic is written, so a
-// fused window and a chain of single-step calls run the very same operations.
-__device__ __forceinline__ void adam_step(float& w, float& m, float& v, float g, float b1,
-                                          float omb1, float b2, float omb2, float eps,
-                                          float lr_bc1, float ibc2) {
-    m = __fmaf_rn(b1, m, __fmul_rn(omb1, g));
-    v = __fmaf_rn(b2, v, __fmul_rn(__fmul_rn(omb2, g), g));
-    const float denom = __fadd_rn(__builtin_amdgcn_sqrtf(__fmul_rn(v, ibc2)), eps);
-    const float upd = __fmul_rn(__fmul_rn(lr_bc1, m), __builtin_amdgcn_rcpf(denom));
-    w = __fsub_rn(w, upd);
-}
 
 constexpr int kAdamThreads = 256;
 constexpr int kAdamH = 4;                          // 16-byte fp32 vectors per thread and array
@@ -151,12 +135,12 @@ __global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, fl
             for (int t = 0; t < WT; ++t) {
                 if (t0 + t < a.W) {
                     const uint32_t gw[2] = {gq[t][h].x, gq[t][h].y};
-                    const float lr_bc1 = a.lr_over_bc1[t0 + t], ibc2 = a.inv_bc2[t0 + t];
+                    const float lr_bc1 = a.s.lr_over_bc1[t0 + t], ibc2 = a.s.inv_bc2[t0 + t];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const uint32_t half = (e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu);
-                        adam_step(ww[e], mm[e], v4_[e], bf16_widen(half), a.beta1, a.one_m_beta1, a.beta2,
-                                  a.one_m_beta2, a.eps, lr_bc1, ibc2);
+                        ld_adam_step(ww[e], mm[e], v4_[e], ld_bf16_widen(half), a.s.beta1, a.s.one_m_beta1, a.s.beta2,
+                                  a.s.one_m_beta2, a.s.eps, lr_bc1, ibc2);
                     }
                 }
             }
@@ -169,8 +153,8 @@ __global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, fl
         for (int64_t e = b0 + threadIdx.x; e < n; e += kAdamThreads) {
             float ww = w[e], mm = m[e], v1 = v[e];
             for (int t = t0; t < t0 + WT && t < a.W; ++t)
-                adam_step(ww, mm, v1, bf16_widen(a.grad[t][e]), a.beta1, a.one_m_beta1, a.beta2,
-                          a.one_m_beta2, a.eps, a.lr_over_bc1[t], a.inv_bc2[t]);
+                ld_adam_step(ww, mm, v1, ld_bf16_widen(a.grad[t][e]), a.s.beta1, a.s.one_m_beta1, a.s.beta2,
+                          a.s.one_m_beta2, a.s.eps, a.s.lr_over_bc1[t], a.s.inv_bc2[t]);
             w[e] = ww;
             m[e] = mm;
             v[e] = v1;
@@ -244,27 +228,15 @@ extern "C" ld_status ld_merge_dense_adam(float* w, float* m, float* v, int64_t n
     if (W == 0 || n == 0) return LD_OK;
     if (!w || !m || !v || !grads_bf16) return LD_ERR_NULL;
     if (!ld_aligned(w, 16) || !ld_aligned(m, 16) || !ld_aligned(v, 16)) return LD_ERR_ALIGN;
+    static_assert(LD_MAX_ADAM_WINDOW <= LD_MAX_ADAM_STEPS, "step table too small");
     AdamArgs a;
-    for (int32_t t = 0; t < LD_MAX_ADAM_WINDOW; ++t) {
-        a.grad[t] = nullptr;
-        a.lr_over_bc1[t] = 0.0f;
-        a.inv_bc2[t] = 0.0f;
-    }
+    for (int32_t t = 0; t < LD_MAX_ADAM_WINDOW; ++t) a.grad[t] = nullptr;
     for (int32_t t = 0; t < W; ++t) {
         if (!grads_bf16[t]) return LD_ERR_NULL;
         if (!ld_aligned(grads_bf16[t], 16)) return LD_ERR_ALIGN;
         a.grad[t] = static_cast<const uint16_t*>(grads_bf16[t]);
-        const double s = static_cast<double>(step0 + 1 + t);
-        const double bc1 = 1.0 - pow(static_cast<double>(beta1), s);
-        const double bc2 = 1.0 - pow(static_cast<double>(beta2), s);
-        a.lr_over_bc1[t] = static_cast<float>(static_cast<double>(lr) / bc1);
-        a.inv_bc2[t] = static_cast<float>(1.0 / bc2);
     }
-    a.beta1 = beta1;
-    a.one_m_beta1 = 1.0f - beta1;
-    a.beta2 = beta2;
-    a.one_m_beta2 = 1.0f - beta2;
-    a.eps = eps;
+    ld_fill_adam_steps(a.s, W, step0, lr, beta1, beta2, eps);
     a.W = W;
     const int64_t blocks = (n + kAdamBlockElems - 1) / kAdamBlockElems;
     if (blocks > INT32_MAX - 8) return LD_ERR_RANGE;

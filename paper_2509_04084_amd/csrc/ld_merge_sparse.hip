@@ -21,67 +21,24 @@
 //              HBM traffic: 8n + 8*sum(K) bytes + the chunk table.
 //  * scatter - one kernel per diff, one thread per record; for windows that
 //              touch only a small part of w.
-#include <limits.h>
-
-#include "ld_common.h"
+#include "ld_sparse_common.h"
 
 namespace {
 
 constexpr int kSub = 8192;                 // elements per wave sub-tile (32 KB of LDS, 5 waves per CU)
 constexpr int kChunkSubs = 6;              // sub-tiles per chunk of the range table
-constexpr int64_t kChunk = static_cast<int64_t>(kSub) * kChunkSubs;
-constexpr int kGroupMax = 64;              // diffs per launch (pointer table travels as a kernel argument)
+static_assert(static_cast<int64_t>(kSub) * kChunkSubs == kChunk, "sub-tiles must tile a chunk");
 constexpr int kWin = 2;                    // 64-record windows per diff loaded ahead
 constexpr int kPre = 10;                   // diffs whose windows are loaded before any is applied
 constexpr int kMargin = 24;                // records the window starts before the interpolated position
-
-struct DiffTable {
-    const int32_t* idx[kGroupMax];
-    const float* val[kGroupMax];
-    int32_t K[kGroupMax];
-};
-
-__device__ __forceinline__ int32_t lower_bound_idx(const int32_t* __restrict__ idx, int32_t lo, int32_t hi,
-                                                   int64_t target) {
-    while (lo < hi) {
-        const int32_t mid = lo + ((hi - lo) >> 1);
-        if (static_cast<int64_t>(idx[mid]) < target) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-
-// ctab[t*(nchunk+1) + b] = number of records of diff t with idx < min(n, b*kChunk).
-// A workgroup covers 256 consecutive boundaries of one diff: two threads bracket
-// the whole run with full searches, then every thread bisects inside the bracket.
-__global__ __launch_bounds__(256) void k_chunks(DiffTable tb, int64_t n, int32_t nchunk,
-                                                int32_t* __restrict__ ctab) {
-    __shared__ int32_t bracket[2];
-    const int32_t b0 = blockIdx.x * 256;
-    const int32_t b = b0 + threadIdx.x;
-    const int t = blockIdx.y;
-    const int32_t* __restrict__ idx = tb.idx[t];
-    const int32_t K = tb.K[t];
-    if (threadIdx.x < 2) {
-        int32_t bb = threadIdx.x == 0 ? b0 : b0 + 255;
-        if (bb > nchunk) bb = nchunk;
-        int64_t target = static_cast<int64_t>(bb) * kChunk;
-        if (target > n) target = n;
-        bracket[threadIdx.x] = lower_bound_idx(idx, 0, K, target);
-    }
-    __syncthreads();
-    if (b > nchunk) return;
-    int64_t target = static_cast<int64_t>(b) * kChunk;
-    if (target > n) target = n;
-    ctab[static_cast<int64_t>(t) * (nchunk + 1) + b] = lower_bound_idx(idx, bracket[0], bracket[1], target);
-}
 
 __device__ __forceinline__ void apply_record(float* tile, int32_t local, float val, float lr) {
     const float p = __fmul_rn(lr, val);        // rounded product: never fused
     tile[local] = __fsub_rn(tile[local], p);
 }
 
-// Applies the records of one diff at positions [p, end) that fall below hi (all of
-// them are at or above the sub-tile's first element), 64 at a time.
+// Applies the records of one diff at positions [p, end) that fall into [lo, hi), 64 at a
+// time, up to the first record at or beyond hi.
 __device__ __forceinline__ void apply_from(float* tile, const int32_t* __restrict__ idx,
                                            const float* __restrict__ val, int32_t p, int32_t end,
                                            int32_t lo, int32_t hi, float lr, int lane) {
@@ -89,7 +46,7 @@ __device__ __forceinline__ void apply_from(float* tile, const int32_t* __restric
         const bool have = p + lane < end;
         const int32_t i = have ? idx[p + lane] : INT_MAX;
         const float v = have ? val[p + lane] : 0.0f;
-        if (i < hi) apply_record(tile, i - lo, v, lr);
+        if (i >= lo && i < hi) apply_record(tile, i - lo, v, lr);
         if (__ballot(i >= hi)) break;
     }
 }
@@ -203,22 +160,6 @@ __global__ __launch_bounds__(256) void k_merge_scatter(float* __restrict__ w,
 }
 
 int32_t sub_tiles(int64_t n) { return static_cast<int32_t>((n + kSub - 1) / kSub); }
-int32_t chunks(int64_t n) { return static_cast<int32_t>((n + kChunk - 1) / kChunk); }
-
-ld_status check_args(float* w, int64_t n, const int32_t* const* idx, const float* const* val,
-                     const int64_t* K, int32_t W) {
-    if (n < 0 || n > INT32_MAX || W < 0 || W > LD_MAX_WINDOW) return LD_ERR_RANGE;
-    if (W == 0) return LD_OK;
-    if (!idx || !val || !K) return LD_ERR_NULL;
-    if (n > 0 && !w) return LD_ERR_NULL;
-    if (!ld_aligned(w, 16)) return LD_ERR_ALIGN;
-    for (int32_t t = 0; t < W; ++t) {
-        if (K[t] < 0 || K[t] > n) return LD_ERR_RANGE;
-        if (K[t] > 0 && (!idx[t] || !val[t])) return LD_ERR_NULL;
-        if (!ld_aligned(idx[t], 4) || !ld_aligned(val[t], 4)) return LD_ERR_ALIGN;
-    }
-    return LD_OK;
-}
 
 }  // namespace
 
@@ -233,7 +174,7 @@ extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t
                                               const float* const* val, const int64_t* K, int32_t W,
                                               float lr, void* workspace, size_t workspace_bytes,
                                               ld_stream stream, int32_t strategy) {
-    const ld_status st = check_args(w, n, idx, val, K, W);
+    const ld_status st = check_diff_args(w, n, idx, val, K, W);
     if (st != LD_OK) return st;
     if (strategy < LD_MERGE_AUTO || strategy > LD_MERGE_SCATTER) return LD_ERR_RANGE;
     if (W == 0 || n == 0) return LD_OK;

@@ -64,6 +64,10 @@ def load() -> ctypes.CDLL:
     lib.ld_merge_sparse_strategy.restype = i32
     lib.ld_merge_dense_adam.argtypes = [vp, vp, vp, i64, vp, i32, i64, f32, f32, f32, f32, vp]
     lib.ld_merge_dense_adam.restype = i32
+    lib.ld_merge_sparse_adam_workspace.argtypes = [i64, i32, vp]
+    lib.ld_merge_sparse_adam_workspace.restype = sz
+    lib.ld_merge_sparse_adam.argtypes = [vp, vp, vp, i64, vp, vp, vp, i32, i64, f32, f32, f32, f32, vp, sz, vp]
+    lib.ld_merge_sparse_adam.restype = i32
     _lib = lib
     return lib
 
@@ -199,3 +203,35 @@ def ld_merge_dense_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grads
                                     ctypes.c_float(lr), ctypes.c_float(beta1), ctypes.c_float(beta2),
                                     ctypes.c_float(eps), _stream(stream))
     _check("ld_merge_dense_adam", st)
+
+
+def ld_merge_sparse_adam_workspace(n: int, K: Sequence[int]) -> int:
+    K = _host(K, np.int64)
+    return int(load().ld_merge_sparse_adam_workspace(int(n), int(K.shape[0]), _hp(K)))
+
+
+def ld_merge_sparse_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, idx: Sequence[torch.Tensor],
+                         val: Sequence[torch.Tensor], step0: int, lr: float, beta1: float, beta2: float,
+                         eps: float, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Replays the sparse diffs (idx[t], val[t]) as Adam steps step0+1.. onto (w, m, v), in place."""
+    lib = load()
+    W = len(idx)
+    if len(val) != W:
+        raise ValueError("idx and val differ in length")
+    if m.numel() != w.numel() or v.numel() != w.numel():
+        raise ValueError("w, m, v differ in size")
+    K = np.array([t.numel() for t in idx], dtype=np.int64)
+    for a, b in zip(idx, val):
+        if a.numel() != b.numel():
+            raise ValueError("idx[t] and val[t] differ in size")
+    ip = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.int32, "idx").value or 0 for t in idx])
+    vp = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.float32, "val").value or 0 for t in val])
+    if workspace is None:
+        workspace = torch.empty(int(lib.ld_merge_sparse_adam_workspace(w.numel(), W, _hp(K))),
+                                dtype=torch.uint8, device=w.device)
+    st = lib.ld_merge_sparse_adam(_dev(w, torch.float32, "w"), _dev(m, torch.float32, "m"),
+                                  _dev(v, torch.float32, "v"), w.numel(), ip, vp, _hp(K), W, int(step0),
+                                  ctypes.c_float(lr), ctypes.c_float(beta1), ctypes.c_float(beta2),
+                                  ctypes.c_float(eps), _dev(workspace, torch.uint8, "workspace"),
+                                  workspace.numel(), _stream(stream))
+    _check("ld_merge_sparse_adam", st)

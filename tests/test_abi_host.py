@@ -103,3 +103,24 @@ def test_dense_argument_errors():
     assert adam(n=-1) == -2 and adam(W=65) == -2 and adam(step0=-1) == -2 and adam(b1=1.0) == -2
     assert adam(m=FAKE + 4) == -5 and adam(g=(ctypes.c_void_p * 2)(FAKE, FAKE + 2)) == -5
     assert adam(W=0) == 0 and adam(n=0) == 0
+
+
+def test_sparse_adam_argument_errors():
+    lib = ld.load()
+    K = np.array([4], np.int64)
+    one = ctypes.c_void_p(256)  # never dereferenced: every call below fails its checks first
+    ptrs = (ctypes.c_void_p * 1)(256)
+    f = ctypes.c_float
+    args = lambda **kw: [kw.get("w", one), kw.get("m", one), kw.get("v", one), kw.get("n", 100), ptrs, ptrs,
+                         _p(K), kw.get("W", 1), kw.get("step0", 0), f(1e-4), f(kw.get("b1", 0.9)), f(0.999), f(1e-8),
+                         kw.get("ws", one), kw.get("wsb", 1 << 20), None]
+    assert lib.ld_merge_sparse_adam(*args(n=-1)) == -2
+    assert lib.ld_merge_sparse_adam(*args(n=1 << 31)) == -2
+    assert lib.ld_merge_sparse_adam(*args(step0=-1)) == -2
+    assert lib.ld_merge_sparse_adam(*args(b1=1.0)) == -2
+    assert lib.ld_merge_sparse_adam(*args(m=ctypes.c_void_p(0))) == -1
+    assert lib.ld_merge_sparse_adam(*args(v=ctypes.c_void_p(8))) == -5
+    assert lib.ld_merge_sparse_adam(*args(ws=ctypes.c_void_p(0))) == -3
+    assert lib.ld_merge_sparse_adam(*args(wsb=0)) == -3
+    assert lib.ld_merge_sparse_adam(*args(W=0)) == 0
+    assert lib.ld_merge_sparse_adam_workspace(1 << 20, 20, _p(np.full(20, 100, np.int64))) >= 20 * 22 * 4

@@ -292,3 +292,81 @@ def test_adam_zero_gradient_and_closed_form():
     want = 1.0 - T * hp["lr"] * cd / (np.abs(cd) + hp["eps"])
     want[cd == 0] = 1.0
     np.testing.assert_allclose(w.cpu().numpy(), want, rtol=3e-6)
+
+
+# ------------------------------------------------- sparse diffs through Adam
+
+@pytest.mark.parametrize("n,W,dens,step0", [(1, 1, 1.0, 0), (7, 3, 0.5, 0), (2047, 4, 0.05, 3), (2049, 5, 0.01, 0),
+                                            (1000003, 6, 0.01, 1000), (300000, 70, 0.004, 2),
+                                            (123457, 3, 1.0, 0), (50000, 4, 0.0, 5)])
+def test_sparse_adam_replay_parity(n, W, dens, step0):
+    rs = np.random.RandomState(n % 1000 + W)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    m0 = np.zeros(n, np.float32) if step0 == 0 else (rs.standard_normal(n) * 1e-4).astype(np.float32)
+    v0 = np.zeros(n, np.float32) if step0 == 0 else (rs.standard_normal(n) ** 2 * 1e-7).astype(np.float32)
+    idxs, vals = [], []
+    for t in range(W):
+        kk = int(round(n * dens)) if t != 1 else min(n, int(round(n * dens * 2)))
+        idxs.append(np.sort(rs.choice(n, kk, replace=False)).astype(np.int32))
+        vals.append((rs.standard_normal(kk) * 1e-3).astype(np.float32))
+    hp = dict(lr=1e-4, **synth.ADAM)
+    print(f"[sparse_adam] n={n} W={W} dens={dens} step0={step0}", flush=True)
+    ref = oracle.sparse_adam_replay(w0, m0, v0, idxs, vals, step0, **hp)
+    gi, gv = [to_gpu(i) for i in idxs], [to_gpu(v) for v in vals]
+    w, m, v = to_gpu(w0), to_gpu(m0), to_gpu(v0)
+    ld.ld_merge_sparse_adam(w, m, v, gi, gv, step0, **hp)
+    torch.cuda.synchronize()
+    for name, a, b in zip("wmv", (w, m, v), ref):
+        a = a.cpu().numpy().astype(np.float64)
+        err = np.abs(a - b.astype(np.float64))
+        assert np.all(err <= 1e-7 + 1e-6 * np.abs(b)), f"{name}: max err {err.max()}"
+    # v never cancels: hold it to a relative bound alone (W roundings of 2^-24 each)
+    a, b = v.cpu().numpy().astype(np.float64), ref[2].astype(np.float64)
+    assert np.all(np.abs(a - b) <= max(1e-6, W * 1.2e-7) * np.abs(b)), "v relative"
+    # the window in one call == one call per diff, bit for bit
+    w2, m2, v2 = to_gpu(w0), to_gpu(m0), to_gpu(v0)
+    for t in range(W):
+        ld.ld_merge_sparse_adam(w2, m2, v2, [gi[t]], [gv[t]], step0 + t, **hp)
+    torch.cuda.synchronize()
+    for a, b in ((w, w2), (m, m2), (v, v2)):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def test_sparse_adam_equals_dense_adam_on_full_diffs():
+    # diffs that record every position with bf16-representable values are dense gradients:
+    # both entry points must then agree bit for bit (they share the per-element step)
+    n, W = 70001, 3
+    rs = np.random.RandomState(9)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    gb = [to_gpu((rs.standard_normal(n) * 1e-3).astype(np.float32)).to(torch.bfloat16) for _ in range(W)]
+    hp = dict(lr=1e-4, **synth.ADAM)
+    w, m, v = to_gpu(w0), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    ld.ld_merge_dense_adam(w, m, v, gb, 0, **hp)
+    allidx = torch.arange(n, dtype=torch.int32, device=DEV)
+    w2, m2, v2 = to_gpu(w0), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    ld.ld_merge_sparse_adam(w2, m2, v2, [allidx] * W, [g.float() for g in gb], 0, **hp)
+    torch.cuda.synchronize()
+    for a, b in ((w, w2), (m, m2), (v, v2)):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def test_sparse_adam_after_compress_resnet_window():
+    # diffs as ld_compress_topk emits them (161 segments of very different sizes)
+    wl = synth.workload("resnet50")
+    W = 4
+    r_gpu = torch.zeros(wl.n, device=DEV)
+    gi, gv = [], []
+    for t in range(W):
+        a, b = ld.ld_compress_topk(to_gpu(synth.gradient(wl, t).numpy()), r_gpu, wl.seg_off, wl.seg_k)
+        gi.append(a)
+        gv.append(b)
+    rs = np.random.RandomState(4)
+    w0 = synth.base_weights(wl.n).numpy()
+    m0 = (rs.standard_normal(wl.n) * 1e-4).astype(np.float32)
+    v0 = (rs.standard_normal(wl.n) ** 2 * 1e-7).astype(np.float32)
+    hp = dict(lr=1e-4, **synth.ADAM)
+    w, m, v = to_gpu(w0), to_gpu(m0), to_gpu(v0)
+    ld.ld_merge_sparse_adam(w, m, v, gi, gv, 10, **hp)
+    torch.cuda.synchronize()
+    ref = oracle.sparse_adam_replay(w0, m0, v0, [i.cpu().numpy() for i in gi], [x.cpu().numpy() for x in gv], 10, **hp)
+    check_adam_close((w, m, v), ref, "resnet50 window")
