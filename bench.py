@@ -100,6 +100,27 @@ class SparseLeg:
     def bytes_merge(self):
         return 8 * self.n + 8 * self.K * self.W
 
+    # -- next row: the same window replayed through Adam on (w, m, v); timed on its own, after the
+    #    timed steps, and not part of `value`
+    def time_sparse_adam(self, reps=3):
+        m = torch.zeros(self.n, dtype=torch.float32, device=self.dev)
+        v = torch.zeros(self.n, dtype=torch.float32, device=self.dev)
+        ws = torch.empty(ld.ld_merge_sparse_adam_workspace(self.n, [self.K] * self.W), dtype=torch.uint8,
+                         device=self.dev)
+        tm = Timer()
+        for i in range(reps + 1):
+            tok = tm.start("sparse_adam")
+            ld.ld_merge_sparse_adam(self.w, m, v, self.idx, self.val, i * self.W, 1e-4, workspace=ws, **synth.ADAM)
+            tm.stop(tok)
+        torch.cuda.synchronize()
+        return float(np.mean(tm.ms()["sparse_adam"][1:]))
+
+    def bytes_sparse_adam(self):
+        return 24 * self.n + 8 * self.K * self.W
+
+    def flops_sparse_adam(self):
+        return 14 * self.n * self.W  # per element and step: 3 (m) + 4 (v) + 3 (root, eps) + 3 (update) + 1
+
     def grad_bytes(self):
         return 4 * self.n * self.W
 
@@ -256,6 +277,7 @@ def main():
     ap.add_argument("--legs", default="sparse,dense",
                     help="comma list of sparse, dense, copycal (copycal: a 1 GiB plain copy, for counter calibration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-next-rows", action="store_true", help="skip the calls measured outside the step")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
@@ -321,6 +343,18 @@ def main():
         share["ld_merge_dense_adam"] = per["adam"]
     if copycal:
         calls["copycal(ld_snapshot_layer, 1 GiB)"] = roof("copycal", 4 * copycal.n)
+    next_rows = {}
+    if sparse and not args.no_next_rows:
+        ms = sparse.time_sparse_adam()
+        log(f"[next row] ld_merge_sparse_adam: {ms:.2f} ms per call (W={sparse.W})")
+        tf = sparse.flops_sparse_adam() / (ms * 1e-3) / 1e12
+        next_rows["ld_merge_sparse_adam"] = {
+            "ms": ms, "algorithmic_bytes": sparse.bytes_sparse_adam(),
+            "hbm_GBps": sparse.bytes_sparse_adam() / (ms * 1e-3) / 1e9,
+            "hbm_frac": sparse.bytes_sparse_adam() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "roofline": {"bound": "alu", "achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
+                         "note": "14 flops per element and step; peak = fp32 vector rate with packed FMA"},
+            "note": "same gpt2xl window replayed through Adam on (w, m, v); not part of `value`"}
     if not share:
         print(json.dumps({"calls": calls}), flush=True)
         return
@@ -346,6 +380,8 @@ def main():
                              f"snapshots per model layer ({len(dense.groups)} calls) + fused Adam replay") if dense else None},
         "roofline": roofline, "calls": calls,
     }
+    if next_rows:
+        out["next_rows"] = next_rows
     if not args.no_cpu_baseline:
         log("[cpu_baseline] timing the oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline()

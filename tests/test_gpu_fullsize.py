@@ -105,6 +105,31 @@ def test_gpt2xl_compress_and_merge_full_size():
     for i in idxs:
         touched[i.to(torch.int64)] = True
     assert torch.equal(w[~touched].view(torch.int32), w_ref[~touched].view(torch.int32))
+    del w_ref
+    # --- the same window replayed through Adam on (w, m, v), checked by the oracle on the same slices
+    _progress("sparse diffs through Adam")
+    hp = dict(lr=1e-4, **synth.ADAM)
+    rs = np.random.RandomState(11)
+    w = synth.base_weights(n, device=DEV, std=wl.w_std)
+    m = torch.randn(n, device=DEV) * 1e-4
+    v = torch.randn(n, device=DEV).square_() * 1e-7
+    state0 = [(w[a:b].cpu().numpy(), m[a:b].cpu().numpy(), v[a:b].cpu().numpy()) for a, b in slices]
+    ld.ld_merge_sparse_adam(w, m, v, idxs, vals, 7, **hp)
+    torch.cuda.synchronize()
+    for (a, b), (w0, m0, v0) in zip(slices, state0):
+        b = min(b, a + 1_500_000)
+        sub_i, sub_v = [], []
+        for ih, vh in zip(idx_h, val_h):
+            p0, p1 = np.searchsorted(ih, a), np.searchsorted(ih, b)
+            sub_i.append((ih[p0:p1] - a).astype(np.int32))
+            sub_v.append(vh[p0:p1])
+        ref = oracle.sparse_adam_replay(w0[:b - a], m0[:b - a], v0[:b - a], sub_i, sub_v, 7, **hp)
+        for name, got, want in zip("wmv", (w, m, v), ref):
+            x = got[a:b].cpu().numpy().astype(np.float64)
+            assert np.all(np.abs(x - want) <= 1e-7 + 1e-6 * np.abs(want)), f"sparse adam {name} slice [{a},{b})"
+        xv = v[a:b].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(xv - ref[2]) <= 1e-6 * np.abs(ref[2])), f"sparse adam v relative, slice [{a},{b})"
+    assert bool(torch.isfinite(w).all())
 
 
 def test_llama7b_snapshot_and_adam_full_size():
