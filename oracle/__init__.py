@@ -14,6 +14,9 @@ Functions (all operate on host memory, single threaded):
 * ``snapshot(src)`` - bit copy of a bf16 layer (Snapshot of Algorithm 2).
 * ``adam_replay(w, m, v, grads, step0, lr, beta1, beta2, eps)`` - dense Adam
   merge (Algorithm 2 "Merge in CPU", Eq. (4)).
+* ``combine_sparse(idx_list, val_list, n, scale)`` - N per-worker record lists
+  combined into one (Sync of Algorithm 1, Eq. (3)): values at equal indices added
+  in worker order.
 * ``sparse_adam_replay(w, m, v, idx_list, val_list, step0, lr, beta1, beta2, eps)``
   - sparse diffs replayed through Adam (Recovery of Algorithm 1 with the update
   the paper names there).
@@ -65,6 +68,8 @@ def _load():
                                                   ctypes.c_int64, ctypes.c_float, ctypes.c_float,
                                                   ctypes.c_float, ctypes.c_float]
         lib.oracle_sparse_adam_replay.restype = ctypes.c_int
+        lib.oracle_combine_sparse.argtypes = [p, p, p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, p, p]
+        lib.oracle_combine_sparse.restype = ctypes.c_int64
         _lib = lib
     return _lib
 
@@ -171,3 +176,23 @@ def sparse_adam_replay(w, m, v, idx_list, val_list, step0: int, lr: float, beta1
     if rc != 0:
         raise ValueError("oracle_sparse_adam_replay: index out of range")
     return w2, m2, v2
+
+
+def combine_sparse(idx_list, val_list, n: int, scale: float = 1.0):
+    """Combines per-worker record lists; returns (idx int32[Kout], val float32[Kout])."""
+    N = len(idx_list)
+    assert len(val_list) == N
+    idxs = [_c(a, np.int32) for a in idx_list]
+    vals = [_c(a, np.float32) for a in val_list]
+    K = np.array([a.shape[0] for a in idxs], dtype=np.int64)
+    for a, b in zip(idxs, vals):
+        assert a.shape == b.shape
+    total = int(K.sum())
+    out_i = np.empty(max(total, 1), dtype=np.int32)
+    out_v = np.empty(max(total, 1), dtype=np.float32)
+    ip = (ctypes.c_void_p * max(N, 1))(*[a.ctypes.data for a in idxs])
+    vp = (ctypes.c_void_p * max(N, 1))(*[a.ctypes.data for a in vals])
+    cnt = _load().oracle_combine_sparse(ip, vp, _ptr(K), N, int(n), ctypes.c_float(scale), _ptr(out_i), _ptr(out_v))
+    if cnt < 0:
+        raise ValueError("oracle_combine_sparse: index out of range or not ascending")
+    return out_i[:cnt].copy(), out_v[:cnt].copy()

@@ -25,6 +25,8 @@
 //   oracle_snapshot : Snapshot(G^n_t) of Algorithm 2 - a bit copy of one layer.
 //   oracle_adam_replay : "Merge in CPU" of Algorithm 2, M <- M + Adam(o_t, G_t)
 //       (Eq. (4)), with the textbook bias-corrected Adam of Kingma & Ba.
+//   oracle_combine_sparse : Sync of Algorithm 1 / Eq. (3) on the all-gathered
+//       per-worker record lists: values at equal indices added in worker order.
 //   oracle_sparse_adam_replay : the Recovery loop of Algorithm 1 with the update
 //       the paper itself names there (decompress, then Adam on model and optimizer
 //       state), for diffs that are sparse.
@@ -203,6 +205,43 @@ int oracle_sparse_adam_replay(float* w, float* m, float* v, int64_t n, const int
         }
     }
     return 0;
+}
+
+// Sync of Algorithm 1 (Eq. (3)) for compressed gradients that arrive as N per-worker
+// record lists (what an all-gather leaves on every rank): one list, ascending in
+// index, holding for every index recorded by at least one worker
+//     scale * (((+0 + v_{r1}) + v_{r2}) + ...)      r1 < r2 < ... the workers that recorded it
+// - each + one fp32 add, in worker order; scale = 1 for a sum, 1/N for a mean.  The paper
+// does not say which; the caller chooses.  Returns the number of records written
+// (out_idx / out_val must hold sum K), or -1 on an index out of range or not ascending.
+int64_t oracle_combine_sparse(const int32_t* const* idx, const float* const* val, const int64_t* K,
+                              int32_t N, int64_t n, float scale, int32_t* out_idx, float* out_val) {
+    std::vector<int64_t> head(static_cast<size_t>(N), 0);
+    int64_t out = 0;
+    for (;;) {
+        // smallest index not yet consumed
+        int64_t cur = -1;
+        for (int32_t r = 0; r < N; ++r) {
+            if (head[r] < K[r]) {
+                const int64_t i = idx[r][head[r]];
+                if (i < 0 || i >= n) return -1;
+                if (head[r] > 0 && idx[r][head[r] - 1] >= i) return -1;
+                if (cur < 0 || i < cur) cur = i;
+            }
+        }
+        if (cur < 0) break;
+        float sum = 0.0f;
+        for (int32_t r = 0; r < N; ++r) {
+            if (head[r] < K[r] && idx[r][head[r]] == cur) {
+                sum = sum + val[r][head[r]];
+                ++head[r];
+            }
+        }
+        out_idx[out] = static_cast<int32_t>(cur);
+        out_val[out] = scale * sum;
+        ++out;
+    }
+    return out;
 }
 
 }  // extern "C"

@@ -563,3 +563,68 @@ def test_sparse_adam_zero_gradient_positions_and_window_semantics():
     w3, _, _ = oracle.sparse_adam_replay(w0, z, z, [idxs[0]], [vals[0]], 0, **hp)
     g = vals[0].astype(np.float64)
     np.testing.assert_allclose(w3[idxs[0]], w0[idxs[0]] - 1e-3 * g / (np.abs(g) + 1e-8), rtol=1e-6, atol=1e-9)
+
+
+# ------------------------------------------------------- combine of per-worker lists
+
+def test_combine_matches_dense_accumulation_and_library_union():
+    n, N = 5000, 6
+    rs = np.random.RandomState(41)
+    idxs, vals = [], []
+    for r in range(N):
+        kk = rs.randint(0, 400)
+        idxs.append(np.sort(rs.choice(n, kk, replace=False)).astype(np.int32))
+        vals.append(rs.standard_normal(kk).astype(np.float32))
+    oi, ov = oracle.combine_sparse(idxs, vals, n)
+    # index set: numpy's union
+    want_idx = np.unique(np.concatenate(idxs))
+    np.testing.assert_array_equal(oi, want_idx)
+    # values: a dense accumulator filled worker after worker with one fp32 add each
+    acc = np.zeros(n, np.float32)
+    for i, v in zip(idxs, vals):
+        acc[i] = acc[i] + v  # indices are distinct inside a list: a plain vector add
+    assert_bits_equal(ov, acc[want_idx])
+    # scale = 1/N (a mean): one more rounding
+    _, ov2 = oracle.combine_sparse(idxs, vals, n, 1.0 / N)
+    assert_bits_equal(ov2, np.float32(1.0 / N) * acc[want_idx])
+
+
+def test_combine_special_cases_and_worker_order():
+    n = 100
+    i1 = np.array([3, 7, 50], np.int32)
+    v1 = np.array([1.5, -2.0, 0.25], np.float32)
+    # one worker: identity
+    oi, ov = oracle.combine_sparse([i1], [v1], n)
+    np.testing.assert_array_equal(oi, i1)
+    assert_bits_equal(ov, v1)
+    # disjoint lists: the sorted union, values untouched
+    i2 = np.array([0, 8, 99], np.int32)
+    v2 = np.array([4.0, 5.0, 6.0], np.float32)
+    oi, ov = oracle.combine_sparse([i1, i2], [v1, v2], n)
+    np.testing.assert_array_equal(oi, [0, 3, 7, 8, 50, 99])
+    assert_bits_equal(ov, np.array([4.0, 1.5, -2.0, 5.0, 0.25, 6.0], np.float32))
+    # the same list four times: every value times four (dyadic: exact); empty lists change nothing
+    e = np.zeros(0, np.int32)
+    oi, ov = oracle.combine_sparse([i1, e, i1, i1, i1], [v1, e.astype(np.float32), v1, v1, v1], n)
+    np.testing.assert_array_equal(oi, i1)
+    assert_bits_equal(ov, 4 * v1)
+    # a sum that cancels to zero stays in the list (presence, not value, decides)
+    oi, ov = oracle.combine_sparse([i1, i1], [v1, -v1], n)
+    np.testing.assert_array_equal(oi, i1)
+    assert_bits_equal(ov, np.zeros(3, np.float32))
+    # worker order: (a + b) + c differs from a + (b + c) in fp32
+    a, b, c = np.float32(1.0), np.float32(2.0 ** -24), np.float32(2.0 ** -24)
+    assert np.float32(np.float32(a + b) + c) != np.float32(a + np.float32(b + c))
+    one = np.array([5], np.int32)
+    _, ov = oracle.combine_sparse([one, one, one], [np.array([a]), np.array([b]), np.array([c])], n)
+    assert_bits_equal(ov, np.array([np.float32(np.float32(a + b) + c)]))
+    _, ov = oracle.combine_sparse([one, one, one], [np.array([b]), np.array([c]), np.array([a])], n)
+    assert_bits_equal(ov, np.array([np.float32(np.float32(b + c) + a)]))
+    # nothing at all
+    oi, ov = oracle.combine_sparse([e, e], [e.astype(np.float32)] * 2, n)
+    assert oi.shape == (0,) and ov.shape == (0,)
+    # malformed input is refused
+    with pytest.raises(ValueError):
+        oracle.combine_sparse([np.array([5, 5], np.int32)], [np.zeros(2, np.float32)], n)
+    with pytest.raises(ValueError):
+        oracle.combine_sparse([np.array([100], np.int32)], [np.zeros(1, np.float32)], n)
