@@ -3,7 +3,7 @@
  *
  * The library turns each training iteration's gradient into a differential
  * checkpoint and merges a window of such differentials onto a dense base
- * checkpoint.  Five operations, all executed by hand-written HIP kernels:
+ * checkpoint.  Six operations, all executed by hand-written HIP kernels:
  *
  *   ld_compress_topk     Comp of Algorithm 1 (Sec. IV-B): the compressed
  *                        gradient that LowDiff reuses as the differential
@@ -18,6 +18,8 @@
  *   ld_merge_dense_adam  "Merge in CPU" of Algorithm 2, M <- M + Adam(o_t, G_t)
  *                        (Eq. (4)): incremental merge of dense diffs into the
  *                        resident replica (kept in HBM here).
+ *   ld_combine_sparse    Sync of Algorithm 1 (Eq. (3)) on all-gathered compressed
+ *                        gradients: per-worker record lists added into one.
  *   ld_merge_sparse_adam Recovery loop of Algorithm 1 with the paper's own update:
  *                        sparse diffs decompressed and merged through Adam into
  *                        model and optimizer state.
@@ -223,6 +225,35 @@ ld_status ld_merge_sparse_adam(float* w, float* m, float* v, int64_t n,
                                const int64_t* K, int32_t W, int64_t step0,
                                float lr, float beta1, float beta2, float eps,
                                void* workspace, size_t workspace_bytes, ld_stream stream);
+
+/* ------------------------------------------------------------------------
+ * ld_combine_sparse - N per-worker record lists combined into one: Sync of
+ * Algorithm 1 (Sec. IV-B; Eq. (3)) applied to compressed gradients as an
+ * all-gather leaves them on every rank.  The output holds, ascending in index,
+ * every index recorded by at least one worker, with
+ *     out_val = fl32(scale * (((+0 + v_r1) + v_r2) + ...))
+ * over the workers r1 < r2 < ... that recorded it - one fp32 add each, in worker
+ * order (scale = 1: sum; 1/N: mean; the paper does not say which).  An index whose
+ * values cancel to zero is still emitted.
+ *
+ *   idx, val   host arrays of N dev pointers; idx[r] int32[K[r]] strictly
+ *              ascending and in [0, n); val[r] fp32[K[r]]
+ *   K          host [N] int64, 0 <= K[r] <= n
+ *   N          0 <= N <= LD_MAX_WORKERS
+ *   n          size of the index space, <= 2^31-1
+ *   out_idx, out_val  dev [out_cap]; records beyond out_cap are not written
+ *              (sum K always suffices)
+ *   out_count  dev int64, 8-byte aligned: the number of distinct indices (compare
+ *              with out_cap to detect a truncated output)
+ *   workspace  dev, 256-byte aligned, ld_combine_sparse_workspace() bytes
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_WORKSPACE, LD_ERR_HIP.
+ */
+#define LD_MAX_WORKERS 64
+size_t    ld_combine_sparse_workspace(int64_t n, int32_t N);
+ld_status ld_combine_sparse(const int32_t* const* idx, const float* const* val, const int64_t* K,
+                            int32_t N, int64_t n, float scale,
+                            int32_t* out_idx, float* out_val, int64_t out_cap, int64_t* out_count,
+                            void* workspace, size_t workspace_bytes, ld_stream stream);
 
 #ifdef __cplusplus
 }

@@ -68,6 +68,10 @@ def load() -> ctypes.CDLL:
     lib.ld_merge_sparse_adam_workspace.restype = sz
     lib.ld_merge_sparse_adam.argtypes = [vp, vp, vp, i64, vp, vp, vp, i32, i64, f32, f32, f32, f32, vp, sz, vp]
     lib.ld_merge_sparse_adam.restype = i32
+    lib.ld_combine_sparse_workspace.argtypes = [i64, i32]
+    lib.ld_combine_sparse_workspace.restype = sz
+    lib.ld_combine_sparse.argtypes = [vp, vp, vp, i32, i64, f32, vp, vp, i64, vp, vp, sz, vp]
+    lib.ld_combine_sparse.restype = i32
     _lib = lib
     return lib
 
@@ -235,3 +239,40 @@ def ld_merge_sparse_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, idx:
                                   ctypes.c_float(eps), _dev(workspace, torch.uint8, "workspace"),
                                   workspace.numel(), _stream(stream))
     _check("ld_merge_sparse_adam", st)
+
+
+def ld_combine_sparse(idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], n: int, scale: float = 1.0,
+                      out_idx: Optional[torch.Tensor] = None, out_val: Optional[torch.Tensor] = None,
+                      out_count: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                      stream=None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Combines N per-worker record lists (values at equal indices added in list order).
+
+    Returns (out_idx, out_val, out_count): the buffers (capacity sum K unless given) and a one-element
+    int64 device tensor with the number of records; nothing is synchronized."""
+    lib = load()
+    N = len(idx)
+    if len(val) != N:
+        raise ValueError("idx and val differ in length")
+    for a, b in zip(idx, val):
+        if a.numel() != b.numel():
+            raise ValueError("idx[r] and val[r] differ in size")
+    K = np.array([t.numel() for t in idx], dtype=np.int64)
+    dev = idx[0].device if N else torch.device("cuda", torch.cuda.current_device())
+    total = int(K.sum())
+    if out_idx is None:
+        out_idx = torch.empty(total, dtype=torch.int32, device=dev)
+    if out_val is None:
+        out_val = torch.empty(total, dtype=torch.float32, device=dev)
+    if out_count is None:
+        out_count = torch.empty(1, dtype=torch.int64, device=dev)
+    cap = min(out_idx.numel(), out_val.numel())
+    ip = (ctypes.c_void_p * max(N, 1))(*[_dev(t, torch.int32, "idx").value or 0 for t in idx])
+    vp = (ctypes.c_void_p * max(N, 1))(*[_dev(t, torch.float32, "val").value or 0 for t in val])
+    if workspace is None:
+        workspace = torch.empty(int(lib.ld_combine_sparse_workspace(int(n), N)), dtype=torch.uint8, device=dev)
+    st = lib.ld_combine_sparse(ip, vp, _hp(K), N, int(n), ctypes.c_float(scale),
+                               _dev(out_idx, torch.int32, "out_idx"), _dev(out_val, torch.float32, "out_val"),
+                               cap, _dev(out_count, torch.int64, "out_count"),
+                               _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    _check("ld_combine_sparse", st)
+    return out_idx, out_val, out_count

@@ -124,3 +124,21 @@ def test_sparse_adam_argument_errors():
     assert lib.ld_merge_sparse_adam(*args(wsb=0)) == -3
     assert lib.ld_merge_sparse_adam(*args(W=0)) == 0
     assert lib.ld_merge_sparse_adam_workspace(1 << 20, 20, _p(np.full(20, 100, np.int64))) >= 20 * 22 * 4
+
+
+def test_combine_argument_errors():
+    lib = ld.load()
+    V = ctypes.c_void_p
+    K = np.array([4, 4], np.int64)
+    ptrs = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    f = ctypes.c_float
+
+    def call(N=2, n=100, idx=ptrs, K=K, oi=FAKE, ov=FAKE, cap=8, cnt=FAKE, ws=FAKE, wsb=1 << 20):
+        return lib.ld_combine_sparse(idx, ptrs, _p(K), N, n, f(1.0), V(oi), V(ov), cap, V(cnt), V(ws), wsb, V(0))
+
+    assert call(n=-1) == -2 and call(n=1 << 31) == -2 and call(N=65) == -2 and call(cap=-1) == -2
+    assert call(K=np.array([4, 101], np.int64)) == -2
+    assert call(cnt=0) == -1 and call(oi=0) == -1 and call(idx=(ctypes.c_void_p * 2)(FAKE, 0)) == -1
+    assert call(cnt=FAKE + 4) == -5 and call(ov=FAKE + 2) == -5
+    assert call(ws=0) == -3 and call(wsb=16) == -3
+    assert lib.ld_combine_sparse_workspace(1 << 20, 8) >= 8 * 22 * 4 + 128 * 4

@@ -370,3 +370,74 @@ def test_sparse_adam_after_compress_resnet_window():
     torch.cuda.synchronize()
     ref = oracle.sparse_adam_replay(w0, m0, v0, [i.cpu().numpy() for i in gi], [x.cpu().numpy() for x in gv], 10, **hp)
     check_adam_close((w, m, v), ref, "resnet50 window")
+
+
+# ------------------------------------------------- combine of per-worker lists
+
+def check_combine(idxs, vals, n, scale=1.0, tag=""):
+    print(f"[combine] {tag} n={n} N={len(idxs)} K={[len(i) for i in idxs][:8]}", flush=True)
+    oi, ov = oracle.combine_sparse(idxs, vals, n, scale)
+    gi, gv, cnt = ld.ld_combine_sparse([to_gpu(i) for i in idxs], [to_gpu(v) for v in vals], n, scale)
+    torch.cuda.synchronize()
+    c = int(cnt.item())
+    assert c == len(oi), f"{tag}: count {c} != {len(oi)}"
+    np.testing.assert_array_equal(gi[:c].cpu().numpy(), oi, err_msg=f"idx {tag}")
+    np.testing.assert_array_equal(bits(gv[:c].cpu().numpy()), bits(ov), err_msg=f"val {tag}")
+
+
+@pytest.mark.parametrize("n,N,dens", [(1, 1, 1.0), (100, 3, 0.3), (8191, 4, 0.05), (8193, 5, 0.5),
+                                      (1000003, 8, 0.01), (3000000, 64, 0.002), (200000, 2, 1.0),
+                                      (50000, 4, 0.0)])
+def test_combine_parity(n, N, dens):
+    rs = np.random.RandomState(n % 997 + N)
+    idxs, vals = [], []
+    for r in range(N):
+        kk = int(round(n * dens)) if r != 1 else min(n, int(round(n * dens * 1.5)))
+        idxs.append(np.sort(rs.choice(n, kk, replace=False)).astype(np.int32))
+        vals.append(rs.standard_normal(kk).astype(np.float32))
+    check_combine(idxs, vals, n, tag="sum")
+    check_combine(idxs, vals, n, scale=1.0 / N, tag="mean")
+
+
+def test_combine_worker_order_cancellation_and_clusters():
+    n = 100000
+    one = np.array([77777], np.int32)
+    a, b, c = np.float32(1.0), np.float32(2.0 ** -24), np.float32(2.0 ** -24)
+    check_combine([one, one, one], [np.array([a]), np.array([b]), np.array([c])], n, tag="order abc")
+    check_combine([one, one, one], [np.array([b]), np.array([c]), np.array([a])], n, tag="order bca")
+    i = np.arange(100, 5000, 7, dtype=np.int32)
+    v = np.random.RandomState(0).standard_normal(len(i)).astype(np.float32)
+    check_combine([i, i], [v, -v], n, tag="cancel")  # zeros stay in the list
+    # all records of every worker packed into one corner, the rest of the index space empty
+    rs = np.random.RandomState(1)
+    idxs = [np.sort(rs.choice(9000, 3000, replace=False)).astype(np.int32) + 40000 for _ in range(5)]
+    vals = [rs.standard_normal(3000).astype(np.float32) for _ in range(5)]
+    check_combine(idxs, vals, n, tag="clustered")
+    # nothing at all, and a single empty worker among full ones
+    e = np.zeros(0, np.int32)
+    check_combine([e, e], [e.astype(np.float32)] * 2, n, tag="empty")
+    check_combine([idxs[0], e, idxs[1]], [vals[0], e.astype(np.float32), vals[1]], n, tag="one empty")
+
+
+def test_combine_of_compressed_diffs_and_truncated_output():
+    # lists as ld_compress_topk emits them for 4 "workers" (different gradients, same segments)
+    wl = synth.workload("resnet50")
+    gi, gv = [], []
+    for t in range(4):
+        r = torch.zeros(wl.n, device=DEV)
+        a, b = ld.ld_compress_topk(to_gpu(synth.gradient(wl, t).numpy()), r, wl.seg_off, wl.seg_k)
+        gi.append(a)
+        gv.append(b)
+    torch.cuda.synchronize()
+    idxs, vals = [x.cpu().numpy() for x in gi], [x.cpu().numpy() for x in gv]
+    check_combine(idxs, vals, wl.n, scale=0.25, tag="resnet50 x4")
+    # an output buffer that is too small: the count still tells the full size, nothing is written past the end
+    oi, ov = oracle.combine_sparse(idxs, vals, wl.n, 0.25)
+    cap = len(oi) // 2
+    out_i = torch.full((cap + 64,), -1, dtype=torch.int32, device=DEV)
+    out_v = torch.zeros(cap + 64, device=DEV)
+    _, _, cnt = ld.ld_combine_sparse(gi, gv, wl.n, 0.25, out_idx=out_i[:cap], out_val=out_v[:cap])
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == len(oi)
+    np.testing.assert_array_equal(out_i[:cap].cpu().numpy(), oi[:cap])
+    assert bool((out_i[cap:] == -1).all())
