@@ -115,6 +115,23 @@ class SparseLeg:
         torch.cuda.synchronize()
         return float(np.mean(tm.ms()["sparse_adam"][1:]))
 
+    # -- next row: the first 8 diffs of the window taken as the record lists of 8 workers (a stand-in:
+    #    same shapes and density as 8 workers' top-k lists) and combined into one synchronized diff
+    def time_combine(self, workers=8, reps=3):
+        idx, val = self.idx[:workers], self.val[:workers]
+        total = sum(t.numel() for t in idx)
+        out_i = torch.empty(total, dtype=torch.int32, device=self.dev)
+        out_v = torch.empty(total, dtype=torch.float32, device=self.dev)
+        cnt = torch.zeros(1, dtype=torch.int64, device=self.dev)
+        ws = torch.empty(ld.ld_combine_sparse_workspace(self.n, workers), dtype=torch.uint8, device=self.dev)
+        tm = Timer()
+        for i in range(reps + 1):
+            tok = tm.start("combine")
+            ld.ld_combine_sparse(idx, val, self.n, 1.0 / workers, out_i, out_v, cnt, ws)
+            tm.stop(tok)
+        torch.cuda.synchronize()
+        return float(np.mean(tm.ms()["combine"][1:])), total, int(cnt.item())
+
     def bytes_sparse_adam(self):
         return 24 * self.n + 8 * self.K * self.W
 
@@ -355,6 +372,15 @@ def main():
             "roofline": {"bound": "alu", "achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
                          "note": "14 flops per element and step; peak = fp32 vector rate with packed FMA"},
             "note": "same gpt2xl window replayed through Adam on (w, m, v); not part of `value`"}
+        ms, k_in, k_out = sparse.time_combine()
+        log(f"[next row] ld_combine_sparse: {ms:.3f} ms per call (8 lists, {k_in:,} records -> {k_out:,})")
+        nb = 8 * k_in + 8 * k_out
+        next_rows["ld_combine_sparse"] = {
+            "ms": ms, "algorithmic_bytes": nb, "records_in": k_in, "records_out": k_out,
+            "roofline": {"bound": "hbm", "achieved": nb / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "note": "8 B per input record + 8 B per output record"},
+            "note": "8 of the window's diffs taken as 8 workers' lists; not part of `value`"}
     if not share:
         print(json.dumps({"calls": calls}), flush=True)
         return

@@ -8,27 +8,39 @@
 //
 // The index space is cut into 8192-element sub-tiles, one wave each, in two passes:
 //   k_combine_count  marks the sub-tile's recorded positions in an LDS bitmap and
-//                    counts them (per sub-tile, and summed per group of 256);
-//   k_combine_scan   scans the (at most 1024) group sums;
-//   k_combine_emit   accumulates the values in a 32 KB LDS tile, list after list (LDS
-//                    operations of one wave complete in order, and inside one list
-//                    the indices are distinct), then writes the marked positions in
-//                    ascending order at the sub-tile's offset.
+//                    counts them;
+//   k_combine_groups / k_combine_scan   scan the counts (inside groups of 1024
+//                    sub-tiles, then the at most 1024 group sums);
+//   k_combine_emit   rebuilds the bitmap, ranks every position among the recorded
+//                    ones and adds the values at their rank in a small LDS array, list
+//                    after list (LDS operations of one wave complete in order, and
+//                    inside one list the indices are distinct), then writes the array
+//                    out as one contiguous run at the sub-tile's offset. A dense tile
+//                    of the sub-tile would cost 32 KB of LDS per wave and leave one
+//                    wave per SIMD; the ranked array takes 7.5 KB.
 // The records of a sub-tile are found as in ld_merge_sparse: chunk table +
-// interpolated 128-record windows, verified. HBM traffic: the records twice, the
-// output once; the dense tile never leaves LDS.
+// interpolated 192-record windows, verified. HBM traffic: the records twice (a third
+// reading comes from L2), the output once.
 #include "ld_sparse_common.h"
 
 namespace {
 
-constexpr int kSub = 8192;                 // elements per wave sub-tile
-constexpr int kChunkSubs = 6;              // sub-tiles per chunk of the range table
+#ifndef LD_CB_SUB
+#define LD_CB_SUB 8192
+#endif
+constexpr int kSub = LD_CB_SUB;                 // elements per wave sub-tile
+constexpr int kChunkSubs = static_cast<int>(kChunk / kSub);  // sub-tiles per chunk of the range table
 static_assert(static_cast<int64_t>(kSub) * kChunkSubs == kChunk, "sub-tiles must tile a chunk");
-constexpr int kWin = 2;                    // 64-record windows per list loaded ahead
+#ifndef LD_CB_WIN
+#define LD_CB_WIN 3
+#endif
+constexpr int kWin = LD_CB_WIN;                    // 64-record windows per list loaded ahead
 constexpr int kPre = 8;                    // lists whose windows are loaded before any is used
-constexpr int kMargin = 24;                // records the window starts before the interpolated position
+constexpr int kMargin = 32;                // records the window starts before the interpolated position
 constexpr int kWords = kSub / 32;          // bitmap words per sub-tile: 256
-constexpr int kSubsPerGroup = 256;
+constexpr int kSubsPerGroup = 1024;         // n <= 2^31-1 gives at most 1024 groups
+constexpr int kCap = 1024;    // distinct indices of a sub-tile accumulated per round
+               // records staged in LDS per round of the emission
 
 // Calls f(t, i, v) for every record (i, v) of list t with lo <= i < hi, list after list
 // (t ascending); all lanes of the wave take part, one record per lane and call.
@@ -114,15 +126,9 @@ __device__ __forceinline__ SubTile sub_tile(int64_t n) {
     return s;
 }
 
-__global__ __launch_bounds__(256) void k_combine_zero(uint32_t* __restrict__ gsum, int32_t ngrp) {
-    const int32_t i = blockIdx.x * 256 + threadIdx.x;
-    if (i < ngrp) gsum[i] = 0;
-}
-
 __global__ __launch_bounds__(LD_WAVE) void k_combine_count(int64_t n, int32_t nchunk, DiffTable tb, int32_t W,
                                                            const int32_t* __restrict__ ctab,
-                                                           uint32_t* __restrict__ counts,
-                                                           uint32_t* __restrict__ gsum) {
+                                                           uint32_t* __restrict__ counts) {
     __shared__ uint32_t bm[kWords];
     const int lane = threadIdx.x;
     const SubTile s = sub_tile(n);
@@ -139,10 +145,30 @@ __global__ __launch_bounds__(LD_WAVE) void k_combine_count(int64_t n, int32_t nc
 #pragma unroll
     for (int j = 0; j < kWords / LD_WAVE; ++j) c += __popc(bm[j * LD_WAVE + lane]);
     c = ld_wave_sum(c);
-    if (lane == 0) {
-        counts[s.sub] = c;
-        if (c) atomicAdd(&gsum[s.sub / kSubsPerGroup], c);
+    if (lane == 0) counts[s.sub] = c;
+}
+
+// One workgroup per group of kSubsPerGroup sub-tiles: counts -> exclusive prefix inside the group
+// (in place), group total -> gsum.
+__global__ __launch_bounds__(256) void k_combine_groups(uint32_t* __restrict__ counts, int32_t nsub,
+                                                        uint32_t* __restrict__ gsum) {
+    __shared__ uint32_t sh[4];
+    constexpr int per = kSubsPerGroup / 256;
+    const int32_t first = blockIdx.x * kSubsPerGroup + threadIdx.x * per;
+    uint32_t x[per], sum = 0;
+#pragma unroll
+    for (int i = 0; i < per; ++i) {
+        x[i] = first + i < nsub ? counts[first + i] : 0u;
+        sum += x[i];
     }
+    uint32_t total;
+    uint32_t before = ld_block_escan256(sum, sh, total);
+#pragma unroll
+    for (int i = 0; i < per; ++i) {
+        if (first + i < nsub) counts[first + i] = before;
+        before += x[i];
+    }
+    if (threadIdx.x == 0) gsum[blockIdx.x] = total;
 }
 
 // Exclusive scan of the group sums (at most 1024 groups: n <= 2^31-1); total -> *out_count.
@@ -167,60 +193,73 @@ __global__ __launch_bounds__(1024) void k_combine_scan(const uint32_t* __restric
 
 __global__ __launch_bounds__(LD_WAVE) void k_combine_emit(int64_t n, int32_t nchunk, DiffTable tb, int32_t W,
                                                           const int32_t* __restrict__ ctab,
-                                                          const uint32_t* __restrict__ counts,
+                                                          const uint32_t* __restrict__ prefix, int32_t nsub,
+                                                          const uint32_t* __restrict__ gsum,
                                                           const uint32_t* __restrict__ goff, float scale,
                                                           int32_t* __restrict__ out_idx,
                                                           float* __restrict__ out_val, int64_t out_cap) {
-    __shared__ float tile[kSub];
-    __shared__ uint32_t bm[kWords];
+    __shared__ uint32_t bm[kWords];      // recorded positions of the sub-tile
+    __shared__ uint16_t wpre[kWords];    // recorded positions before each bitmap word
+    __shared__ float acc[kCap];          // sums, at the rank of their position among the recorded ones
+    __shared__ uint16_t accq[kCap];      // ... and the positions themselves
     const int lane = threadIdx.x;
     const SubTile s = sub_tile(n);
     if (!s.live) return;
-    // records written before this sub-tile: its group's offset + the counts of the group's earlier sub-tiles
+    // records written before this sub-tile: its group's offset + its prefix inside the group; its own
+    // count is the distance to the next prefix (or to the group's total)
     const int32_t grp = static_cast<int32_t>(s.sub / kSubsPerGroup);
-    const int32_t g_first = grp * kSubsPerGroup, in_grp = static_cast<int32_t>(s.sub) - g_first;
-    uint32_t before = 0;
-#pragma unroll
-    for (int j = 0; j < kSubsPerGroup / LD_WAVE; ++j) {
-        const int32_t q = j * LD_WAVE + lane;
-        before += q < in_grp ? counts[g_first + q] : 0u;
-    }
-    const uint32_t mine = counts[s.sub];
+    const uint32_t before = prefix[s.sub];
+    const bool last_of_group = (s.sub + 1) % kSubsPerGroup == 0 || s.sub + 1 >= nsub;
+    const uint32_t mine = (last_of_group ? gsum[grp] : prefix[s.sub + 1]) - before;
     if (mine == 0) return;  // nothing recorded in this sub-tile
-#pragma unroll
-    for (int j = 0; j < kSub / 4 / LD_WAVE; ++j)
-        reinterpret_cast<ld_f32x4*>(tile)[j * LD_WAVE + lane] = ld_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    const int64_t off = static_cast<int64_t>(goff[grp]) + before;
 #pragma unroll
     for (int j = 0; j < kWords / LD_WAVE; ++j) bm[j * LD_WAVE + lane] = 0;
-    __syncthreads();  // one wave: orders the vector fill before the scalar updates
-    sweep_records<true>(tb, W, ctab, nchunk, s.sub, s.lo, s.hi, lane, [&](int, int32_t i, float v) {
+    __syncthreads();  // one wave: orders the fill before the marks
+    sweep_records<false>(tb, W, ctab, nchunk, s.sub, s.lo, s.hi, lane, [&](int, int32_t i, float) {
         const uint32_t q = static_cast<uint32_t>(i - s.lo);
-        tile[q] = __fadd_rn(tile[q], v);
         atomicOr(&bm[q >> 5], 1u << (q & 31));
     });
     __syncthreads();
-    const int64_t off = static_cast<int64_t>(goff[grp]) + ld_wave_sum(before);
-    // lane l owns bitmap words 4l .. 4l+3, i.e. positions 128 l .. 128 l + 127: ascending in the lane number
-    uint32_t wd[kWords / LD_WAVE], c = 0;
+    {  // lane l owns bitmap words 4l .. 4l+3
+        uint32_t c[kWords / LD_WAVE], sum = 0;
 #pragma unroll
-    for (int j = 0; j < kWords / LD_WAVE; ++j) {
-        wd[j] = bm[lane * (kWords / LD_WAVE) + j];
-        c += __popc(wd[j]);
-    }
-    int64_t pos = off + (ld_wave_iscan(c) - c);
-#pragma unroll
-    for (int j = 0; j < kWords / LD_WAVE; ++j) {
-        uint32_t bits = wd[j];
-        while (bits) {
-            const int b = __builtin_ctz(bits);
-            bits &= bits - 1;
-            const int32_t q = (lane * (kWords / LD_WAVE) + j) * 32 + b;
-            if (pos < out_cap) {
-                out_idx[pos] = s.lo + q;
-                out_val[pos] = __fmul_rn(scale, tile[q]);
-            }
-            ++pos;
+        for (int j = 0; j < kWords / LD_WAVE; ++j) {
+            c[j] = __popc(bm[lane * (kWords / LD_WAVE) + j]);
+            sum += c[j];
         }
+        uint32_t run = ld_wave_iscan(sum) - sum;
+#pragma unroll
+        for (int j = 0; j < kWords / LD_WAVE; ++j) {
+            wpre[lane * (kWords / LD_WAVE) + j] = static_cast<uint16_t>(run);
+            run += c[j];
+        }
+    }
+    // Rounds of kCap distinct indices (one round unless the sub-tile is crowded): the values are added,
+    // list after list, at the rank of their position; then the round is written out as one run.
+#pragma unroll 1
+    for (uint32_t r0 = 0; r0 < mine; r0 += kCap) {
+#pragma unroll
+        for (int j = 0; j < kCap / LD_WAVE; ++j) acc[j * LD_WAVE + lane] = 0.0f;
+        __syncthreads();
+        sweep_records<true>(tb, W, ctab, nchunk, s.sub, s.lo, s.hi, lane, [&](int, int32_t i, float v) {
+            const uint32_t q = static_cast<uint32_t>(i - s.lo);
+            const uint32_t rank = wpre[q >> 5] + __popc(bm[q >> 5] & ((1u << (q & 31)) - 1u));
+            if (rank - r0 < static_cast<uint32_t>(kCap)) {
+                acc[rank - r0] = __fadd_rn(acc[rank - r0], v);
+                accq[rank - r0] = static_cast<uint16_t>(q);
+            }
+        });
+        __syncthreads();
+        const uint32_t cnt = mine - r0 < static_cast<uint32_t>(kCap) ? mine - r0 : static_cast<uint32_t>(kCap);
+        for (uint32_t i = lane; i < cnt; i += LD_WAVE) {
+            const int64_t pos = off + r0 + i;
+            if (pos < out_cap) {
+                out_idx[pos] = s.lo + static_cast<int32_t>(accq[i]);
+                out_val[pos] = __fmul_rn(scale, acc[i]);
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -290,11 +329,12 @@ extern "C" ld_status ld_combine_sparse(const int32_t* const* idx, const float* c
     }
     const int32_t nchunk = chunks(n);
     const dim3 grid(static_cast<uint32_t>((nsub + 7) / 8 * 8)), wave(LD_WAVE);
-    k_combine_zero<<<dim3((ngrp + 255) / 256), dim3(256), 0, s>>>(gsum, ngrp);
     k_chunks<<<dim3((nchunk + 1 + 255) / 256, N), dim3(256), 0, s>>>(tb, n, nchunk, ctab);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
-    k_combine_count<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts, gsum);
+    k_combine_count<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts);
+    k_combine_groups<<<dim3(ngrp), dim3(256), 0, s>>>(counts, nsub, gsum);
     k_combine_scan<<<dim3(1), dim3(1024), 0, s>>>(gsum, goff, ngrp, out_count);
-    k_combine_emit<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts, goff, scale, out_idx, out_val, out_cap);
+    k_combine_emit<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts, nsub, gsum, goff, scale, out_idx, out_val,
+                                         out_cap);
     return ld_launch_status();
 }

@@ -276,3 +276,7 @@ def ld_combine_sparse(idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], 
                                _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
     _check("ld_combine_sparse", st)
     return out_idx, out_val, out_count
+
+
+def ld_combine_sparse_workspace(n: int, N: int) -> int:
+    return int(load().ld_combine_sparse_workspace(int(n), int(N)))

@@ -17,7 +17,7 @@ import sqlite3
 import sys
 
 OURS = ("k_main", "k_prep", "k_upload", "k_hist", "k_bin", "k_gather", "k_select", "k_emit", "k_full_",
-        "k_chunks", "k_merge_", "k_sparse_adam", "k_snapshot", "k_adam")
+        "k_chunks", "k_merge_", "k_sparse_adam", "k_combine_", "k_snapshot", "k_adam")
 
 
 def _short(name: str) -> str:
