@@ -178,3 +178,40 @@ def test_llama7b_snapshot_and_adam_full_size():
         assert np.all(np.abs(xv - vr) <= 2e-6 * np.abs(vr)), f"v relative, slice [{lo},{hi})"
     # every element moved by a finite amount (no slice skipped by the launch shape)
     assert bool(torch.isfinite(w).all()) and bool((v > 0).sum() > 0.99 * n)
+
+
+def test_gpt2s_config_full_size():
+    """Config 3 whole: GPT-2-small-shaped, 124 M parameters, density 0.1 %, a 100-diff window."""
+    wl = synth.workload("gpt2s")
+    off, k = wl.seg_off, wl.seg_k
+    n = wl.n
+    r_cpu = np.zeros(n, np.float32)
+    r_gpu = torch.zeros(n, device=DEV)
+    idxs, vals = [], []
+    for t in range(2):  # two chained diffs, every segment redone by the oracle
+        _progress(f"gpt2s compress t={t}")
+        g = synth.gradient(wl, t).numpy()
+        oi, ov, r_cpu = oracle.topk_ef(g, r_cpu, off, k, select=True)
+        gi, gv = ld.ld_compress_topk(torch.from_numpy(g).to(DEV), r_gpu, off, k)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(gi.cpu().numpy(), oi, err_msg=f"idx t={t}")
+        np.testing.assert_array_equal(bits(gv.cpu().numpy()), bits(ov), err_msg=f"val t={t}")
+        np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(r_cpu), err_msg=f"residual t={t}")
+        idxs.append(oi)
+        vals.append(ov)
+    # the rest of the 100-diff window: random ascending lists of the same density and scale
+    _progress("gpt2s window merge")
+    rs = np.random.RandomState(3)
+    K = int(k.astype(np.int64).sum())
+    for t in range(2, wl.window):
+        i = np.unique(rs.randint(0, n, size=K)).astype(np.int32)
+        idxs.append(i)
+        vals.append((rs.standard_t(3, size=len(i)) * 1e-3).astype(np.float32))
+    w0 = synth.base_weights(n).numpy()
+    ref = oracle.merge_sparse(w0, idxs, vals, wl.lr)
+    for strategy in (ld.LD_MERGE_AUTO, ld.LD_MERGE_SWEEP):
+        w = torch.from_numpy(w0).to(DEV)
+        ld.ld_merge_sparse(w, [torch.from_numpy(i).to(DEV) for i in idxs], [torch.from_numpy(v).to(DEV) for v in vals],
+                           wl.lr, strategy=strategy)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref), err_msg=f"merge strategy {strategy}")
