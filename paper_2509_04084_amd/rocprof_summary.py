@@ -3,13 +3,17 @@
 
     python3 -m paper_2509_04084_amd.rocprof_summary trace  <db>            # --kernel-trace run
     python3 -m paper_2509_04084_amd.rocprof_summary pmc    <db> [<db> ..]  # --pmc runs (one counter each)
+    python3 -m paper_2509_04084_amd.rocprof_summary traffic <sparse pmc summary> <dense pmc summary>
 
 ``trace`` prints calls / total / average / min / max duration per kernel of this
 library (kernels of other libraries, e.g. the input generators, are left out
 unless ``--all`` is given).  ``pmc`` prints the average counter value per launch
 for every kernel and counter found, in MiB when the counter is FETCH_SIZE or
-WRITE_SIZE (rocprofv3 reports those in KiB).  The output is what the files under
-``profiles/`` hold.
+WRITE_SIZE (rocprofv3 reports those in KiB).  ``traffic`` turns two such ``pmc``
+summaries of ``bench.py`` (legs ``sparse,copycal`` and ``dense,copycal``) into HBM
+bytes per entry-point call: every counter is scaled by what it reads for the 1 GiB
+plain copy of the copycal leg, and the kernels of an entry point are added up.  The
+output is what the files under ``profiles/`` hold.
 """
 from __future__ import annotations
 
@@ -58,7 +62,51 @@ def pmc(db_paths) -> str:
     return "\n".join(out)
 
 
+COMPRESS_KERNELS = ("k_upload", "k_prep", "k_main", "k_hist", "k_bin", "k_gather", "k_select", "k_emit",
+                    "k_full_level<1>", "k_full_level<2>", "k_full_level<3>", "k_full_count", "k_full_emit")
+
+
+def _table(path):
+    rows = {}
+    with open(path) as f:
+        for line in f.read().splitlines()[1:]:
+            p = line.split()
+            if len(p) >= 5 and p[1] in ("FETCH_SIZE", "WRITE_SIZE"):
+                rows[(p[0], p[1])] = (int(p[2]), float(p[3]))  # launches, MiB per launch
+    return rows
+
+
+def traffic(sparse_txt: str, dense_txt: str, compress_calls: int = 20, snapshot_iters: int = 4) -> str:
+    mib = 1 << 20
+    S, D = _table(sparse_txt), _table(dense_txt)
+    # calibration copy: the only k_snapshot launch of the sparse run moves 1 GiB in and 1 GiB out
+    ff = 1024.0 / S[("k_snapshot", "FETCH_SIZE")][1]
+    fw = 1024.0 / S[("k_snapshot", "WRITE_SIZE")][1]
+
+    def total(rows, names, calls):
+        f = sum(rows[(k, "FETCH_SIZE")][0] * rows[(k, "FETCH_SIZE")][1] for k in names if (k, "FETCH_SIZE") in rows)
+        w = sum(rows[(k, "WRITE_SIZE")][0] * rows[(k, "WRITE_SIZE")][1] for k in names if (k, "WRITE_SIZE") in rows)
+        return (f * ff + w * fw) / calls * mib
+
+    snap = [k for k in ("k_snapshot", "k_snapshot_batch")]
+    sf = sum(D[(k, "FETCH_SIZE")][0] * D[(k, "FETCH_SIZE")][1] for k in snap if (k, "FETCH_SIZE") in D) * ff
+    sw = sum(D[(k, "WRITE_SIZE")][0] * D[(k, "WRITE_SIZE")][1] for k in snap if (k, "WRITE_SIZE") in D) * fw
+    out = {
+        "ld_compress_topk": total(S, COMPRESS_KERNELS, compress_calls),
+        "ld_merge_sparse": total(S, ("k_chunks", "k_merge_sweep"), 1),
+        "ld_snapshot_layers": (sf + sw - 2048.0) / snapshot_iters * mib,  # minus the calibration copy
+        "ld_merge_dense_adam": total(D, tuple({k for (k, _c) in D if k.startswith("k_adam")}), 1),
+    }
+    lines = [f"# calibration (1 GiB plain copy): FETCH_SIZE x {ff:.3f}, WRITE_SIZE x {fw:.3f}"]
+    for k, v in out.items():
+        lines.append(f"traffic {k} {round(v)}")
+    return "\n".join(lines)
+
+
 def main(argv) -> int:
+    if len(argv) >= 4 and argv[1] == "traffic":
+        print(traffic(argv[2], argv[3]))
+        return 0
     if len(argv) < 3 or argv[1] not in ("trace", "pmc"):
         print(__doc__)
         return 2
