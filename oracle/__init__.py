@@ -70,6 +70,11 @@ def _load():
         lib.oracle_sparse_adam_replay.restype = ctypes.c_int
         lib.oracle_combine_sparse.argtypes = [p, p, p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, p, p]
         lib.oracle_combine_sparse.restype = ctypes.c_int64
+        d = ctypes.c_double
+        lib.oracle_wasted_time.argtypes = [d] * 10
+        lib.oracle_wasted_time.restype = d
+        lib.oracle_critical_interval.argtypes = [d] * 6
+        lib.oracle_critical_interval.restype = d
         _lib = lib
     return _lib
 
@@ -196,3 +201,13 @@ def combine_sparse(idx_list, val_list, n: int, scale: float = 1.0):
     if cnt < 0:
         raise ValueError("oracle_combine_sparse: index out of range or not ascending")
     return out_i[:cnt].copy(), out_v[:cnt].copy()
+
+
+def wasted_time(N, T, M, tau, f, b, R_F, R_B, C_F, C_B) -> float:
+    """Expected wasted GPU time T_w(f, b) of Sec. V-C, Eq. (10)."""
+    return float(_load().oracle_wasted_time(N, T, M, tau, f, b, R_F, R_B, C_F, C_B))
+
+
+def critical_interval(M, tau, b, R_B, C_F, C_B) -> float:
+    """f_c(b) of Eq. (11): the stationary point of T_w in f."""
+    return float(_load().oracle_critical_interval(M, tau, b, R_B, C_F, C_B))

@@ -25,6 +25,8 @@
 //   oracle_snapshot : Snapshot(G^n_t) of Algorithm 2 - a bit copy of one layer.
 //   oracle_adam_replay : "Merge in CPU" of Algorithm 2, M <- M + Adam(o_t, G_t)
 //       (Eq. (4)), with the textbook bias-corrected Adam of Kingma & Ba.
+//   oracle_wasted_time / oracle_critical_interval : the configuration model of
+//       Sec. V-C, Eqs. (8)-(12), written term by term.
 //   oracle_combine_sparse : Sync of Algorithm 1 / Eq. (3) on the all-gathered
 //       per-worker record lists: values at equal indices added in worker order.
 //   oracle_sparse_adam_replay : the Recovery loop of Algorithm 1 with the update
@@ -242,6 +244,27 @@ int64_t oracle_combine_sparse(const int32_t* const* idx, const float* const* val
         ++out;
     }
     return out;
+}
+
+// Expected wasted GPU time of a run, Eq. (10) of Sec. V-C, for a full-checkpoint interval of f
+// iterations and b differentials per batched checkpoint (1 <= b <= f):
+//   failures  N*T/M  times  [ half a batching interval of lost work, b*tau/2
+//                             + one full-checkpoint restore, R_F
+//                             + half of the (f/b - 1) batched differentials replayed, R_B each ]
+//   + the writes: T/(f*tau) full checkpoints at C_F each and (f/b - 1) times as many batched
+//     differentials at C_B each, on all N GPUs.
+double oracle_wasted_time(double N, double T, double M, double tau, double f, double b, double R_F,
+                          double R_B, double C_F, double C_B) {
+    const double n_failures = T / M;
+    const double per_failure = b * tau / 2.0 + R_F + (R_B / 2.0) * (f / b - 1.0);
+    const double n_full = T / (f * tau);
+    const double n_diff = n_full * (f / b - 1.0);
+    return N * n_failures * per_failure + N * n_full * C_F + N * n_diff * C_B;
+}
+
+// The interval at which dT_w/df = 0 for a given b, Eq. (11).
+double oracle_critical_interval(double M, double tau, double b, double R_B, double C_F, double C_B) {
+    return std::sqrt(2.0 * M * b * (C_F - C_B) / (tau * R_B));
 }
 
 }  // extern "C"

@@ -628,3 +628,37 @@ def test_combine_special_cases_and_worker_order():
         oracle.combine_sparse([np.array([5, 5], np.int32)], [np.zeros(2, np.float32)], n)
     with pytest.raises(ValueError):
         oracle.combine_sparse([np.array([100], np.int32)], [np.zeros(1, np.float32)], n)
+
+
+# ------------------------------------------------------- configuration model (Sec. V-C)
+
+def test_wasted_time_model_stationary_point_limits_and_textbook_case():
+    P = dict(N=32.0, T=3.0e5, M=3600.0, tau=2.1)
+    R_F, R_B, C_F, C_B = 12.0, 0.9, 40.0, 1.5
+    b = 3.0
+    Tw = lambda f, b=b, **kw: oracle.wasted_time(f=f, b=b, R_F=R_F, R_B=kw.get("R_B", R_B), C_F=kw.get("C_F", C_F),
+                                                 C_B=kw.get("C_B", C_B), **{**P, **{k: v for k, v in kw.items() if k in P}})
+    # Eq. (11) is the stationary point of Eq. (10) in f, and a minimum
+    fc = oracle.critical_interval(P["M"], P["tau"], b, R_B, C_F, C_B)
+    h = 1e-3 * fc
+    d1 = (Tw(fc + h) - Tw(fc - h)) / (2 * h)
+    d2 = (Tw(fc + h) - 2 * Tw(fc) + Tw(fc - h)) / (h * h)
+    scale = Tw(fc) / fc
+    assert abs(d1) < 1e-6 * scale and d2 > 0
+    assert Tw(fc) < Tw(0.5 * fc) and Tw(fc) < Tw(2 * fc)
+    # linear in the number of GPUs and in the run length
+    assert abs(Tw(30.0, N=64.0) - 2 * Tw(30.0)) < 1e-9 * Tw(30.0)
+    assert abs(Tw(30.0, T=6.0e5) - 2 * Tw(30.0)) < 1e-9 * Tw(30.0)
+    # no failures (M -> infinity): only the write costs remain, N*T/(f*tau) * (C_F + (f/b - 1) C_B)
+    f = 30.0
+    want = P["N"] * P["T"] / (f * P["tau"]) * (C_F + (f / b - 1) * C_B)
+    assert abs(Tw(f, M=1e300) - want) < 1e-9 * want
+    # b = f: no differential checkpoints at all - the classical single-level model, whose optimum
+    # interval is Young's sqrt(2 * M * C) (in time units): f * tau = sqrt(2 * M * C_F)
+    young = np.sqrt(2 * P["M"] * C_F) / P["tau"]
+    g = lambda f: oracle.wasted_time(f=f, b=f, R_F=R_F, R_B=R_B, C_F=C_F, C_B=C_B, **P)
+    hh = 1e-3 * young
+    assert abs((g(young + hh) - g(young - hh)) / (2 * hh)) < 1e-6 * g(young) / young
+    # every term by hand for one small case: N=2, T=100, M=50, tau=1, f=10, b=2, R_F=3, R_B=1, C_F=4, C_B=0.5
+    #   failures 2: each loses 1 + 3 + 0.5*4 = 6 -> 2 GPUs * 2 * 6 = 24; 10 full ckpts * 4 * 2 = 80; 40 diffs * 0.5 * 2 = 40
+    assert abs(oracle.wasted_time(2, 100, 50, 1, 10, 2, 3, 1, 4, 0.5) - 144.0) < 1e-12
