@@ -255,6 +255,35 @@ ld_status ld_combine_sparse(const int32_t* const* idx, const float* const* val, 
                             int32_t* out_idx, float* out_val, int64_t out_cap, int64_t* out_count,
                             void* workspace, size_t workspace_bytes, ld_stream stream);
 
+/* ------------------------------------------------------------------------
+ * Checkpointing configuration model (Sec. V-C).  Host arithmetic only; nothing is
+ * enqueued.  f = full-checkpoint interval in iterations, b = differentials per
+ * batched checkpoint, 1 <= b <= f.
+ *
+ *   ld_config_wasted_time        T_w(f, b), Eq. (10):
+ *       (N T / M) [ b tau / 2 + R_F + (R_B / 2)(f/b - 1) ] + (N T / (f tau)) [ C_F + C_B (f/b - 1) ]
+ *   ld_config_critical_interval  f_c(b) = sqrt( 2 M b (C_F - C_B) / (tau R_B) ), Eq. (11)
+ *   ld_config_select             Eq. (12): index of the candidate (f[i], b[i]) with the smallest
+ *                                T_w, R_B[i] and C_B[i] being the costs measured for b[i];
+ *                                wasted (optional, [n_cand]) receives every T_w
+ * R_B: recovery time of one batched differential (read + decompress + replay of b diffs),
+ * C_B: its write cost (Eqs. (8), (9)); all times in one unit (seconds).
+ * Invalid arguments give NaN (the first two) or -1 (select); candidates whose T_w is NaN
+ * are skipped.
+ */
+typedef struct ld_config_params {
+    double N;    /* GPUs                                   */
+    double T;    /* failure-free training duration         */
+    double M;    /* mean time between failures             */
+    double tau;  /* average iteration time                 */
+    double R_F;  /* time to restore one full checkpoint    */
+    double C_F;  /* time to write one full checkpoint      */
+} ld_config_params;
+double  ld_config_wasted_time(const ld_config_params* p, double f, double b, double R_B, double C_B);
+double  ld_config_critical_interval(const ld_config_params* p, double b, double R_B, double C_B);
+int32_t ld_config_select(const ld_config_params* p, int32_t n_cand, const int32_t* f, const int32_t* b,
+                         const double* R_B, const double* C_B, double* wasted /* may be NULL */);
+
 #ifdef __cplusplus
 }
 #endif

@@ -72,6 +72,13 @@ def load() -> ctypes.CDLL:
     lib.ld_combine_sparse_workspace.restype = sz
     lib.ld_combine_sparse.argtypes = [vp, vp, vp, i32, i64, f32, vp, vp, i64, vp, vp, sz, vp]
     lib.ld_combine_sparse.restype = i32
+    dbl = ctypes.c_double
+    lib.ld_config_wasted_time.argtypes = [vp, dbl, dbl, dbl, dbl]
+    lib.ld_config_wasted_time.restype = dbl
+    lib.ld_config_critical_interval.argtypes = [vp, dbl, dbl, dbl]
+    lib.ld_config_critical_interval.restype = dbl
+    lib.ld_config_select.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.ld_config_select.restype = i32
     _lib = lib
     return lib
 
@@ -280,3 +287,28 @@ def ld_combine_sparse(idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], 
 
 def ld_combine_sparse_workspace(n: int, N: int) -> int:
     return int(load().ld_combine_sparse_workspace(int(n), int(N)))
+
+
+class ConfigParams(ctypes.Structure):
+    """ld_config_params of lowdiff.h (Sec. V-C): N, T, M, tau, R_F, C_F."""
+    _fields_ = [(k, ctypes.c_double) for k in ("N", "T", "M", "tau", "R_F", "C_F")]
+
+
+def ld_config_wasted_time(p: ConfigParams, f: float, b: float, R_B: float, C_B: float) -> float:
+    return float(load().ld_config_wasted_time(ctypes.byref(p), f, b, R_B, C_B))
+
+
+def ld_config_critical_interval(p: ConfigParams, b: float, R_B: float, C_B: float) -> float:
+    return float(load().ld_config_critical_interval(ctypes.byref(p), b, R_B, C_B))
+
+
+def ld_config_select(p: ConfigParams, f: Sequence[int], b: Sequence[int], R_B: Sequence[float],
+                     C_B: Sequence[float]) -> Tuple[int, np.ndarray]:
+    """Index of the candidate (f[i], b[i]) with the smallest wasted time, and every T_w."""
+    fa, ba = _host(f, np.int32), _host(b, np.int32)
+    ra, ca = _host(R_B, np.float64), _host(C_B, np.float64)
+    if not (len(fa) == len(ba) == len(ra) == len(ca)):
+        raise ValueError("candidate arrays differ in length")
+    out = np.empty(len(fa), np.float64)
+    i = load().ld_config_select(ctypes.byref(p), len(fa), _hp(fa), _hp(ba), _hp(ra), _hp(ca), _hp(out))
+    return int(i), out

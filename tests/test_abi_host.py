@@ -142,3 +142,30 @@ def test_combine_argument_errors():
     assert call(cnt=FAKE + 4) == -5 and call(ov=FAKE + 2) == -5
     assert call(ws=0) == -3 and call(wsb=16) == -3
     assert lib.ld_combine_sparse_workspace(1 << 20, 8) >= 8 * 22 * 4 + 128 * 4
+
+
+def test_config_model_matches_oracle():
+    import oracle
+    P = dict(N=32.0, T=3.0e5, M=3600.0, tau=2.1, R_F=12.0, C_F=40.0)
+    p = ld.ConfigParams(**P)
+    cand_f, cand_b, R_B, C_B = [], [], [], []
+    for f in (10, 30, 50, 100):
+        for b in (1, 2, 3, 4, 5, 6):
+            cand_f.append(f)
+            cand_b.append(b)
+            R_B.append(0.3 * b + 0.05)      # replay of b diffs + a fixed read latency
+            C_B.append(0.8 + 0.25 * b)      # one I/O request + b records
+    best, tw = ld.ld_config_select(p, cand_f, cand_b, R_B, C_B)
+    want = [oracle.wasted_time(P["N"], P["T"], P["M"], P["tau"], f, b, P["R_F"], rb, P["C_F"], cb)
+            for f, b, rb, cb in zip(cand_f, cand_b, R_B, C_B)]
+    np.testing.assert_allclose(tw, want, rtol=1e-12)
+    assert best == int(np.argmin(want))
+    for b, rb, cb in ((1, 0.35, 1.05), (4, 1.25, 1.8)):
+        got = ld.ld_config_critical_interval(p, b, rb, cb)
+        assert abs(got - oracle.critical_interval(P["M"], P["tau"], b, rb, P["C_F"], cb)) < 1e-12 * got
+        assert abs(ld.ld_config_wasted_time(p, got, b, rb, cb)
+                   - oracle.wasted_time(P["N"], P["T"], P["M"], P["tau"], got, b, P["R_F"], rb, P["C_F"], cb)) < 1e-9
+    # invalid arguments
+    assert np.isnan(ld.ld_config_wasted_time(p, 2.0, 3.0, 1.0, 1.0))         # b > f
+    assert np.isnan(ld.ld_config_critical_interval(p, 2.0, 1.0, 50.0))       # C_B >= C_F
+    assert ld.load().ld_config_select(None, 1, None, None, None, None, None) == -1
