@@ -186,6 +186,19 @@ class DenseLeg:
         tm.stop(tok)
         self.step0 += self.W
 
+    # -- next row: the paper's snapshot destination, pinned host memory (bound by the host link, not HBM)
+    def time_snapshot_to_host(self, reps=3):
+        lo, hi = self.layers[-1]  # the head: 131 M elements, 262 MB
+        src = self.src[0][lo:hi]
+        dst = torch.empty(hi - lo, dtype=torch.bfloat16).pin_memory()
+        tm = Timer()
+        for _ in range(reps + 1):
+            tok = tm.start("to_host")
+            ld.ld_snapshot_layer(src, dst)
+            tm.stop(tok)
+        torch.cuda.synchronize()
+        return float(np.mean(tm.ms()["to_host"][1:])), 2 * (hi - lo)
+
     def bytes_snapshot_iter(self):
         return 4 * self.n
 
@@ -381,6 +394,13 @@ def main():
                          "frac": nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "note": "8 B per input record + 8 B per output record"},
             "note": "8 of the window's diffs taken as 8 workers' lists; not part of `value`"}
+    if dense and not args.no_next_rows:
+        ms, nb = dense.time_snapshot_to_host()
+        log(f"[next row] ld_snapshot_layer into pinned host memory: {ms:.2f} ms for {nb / 1e6:.0f} MB")
+        next_rows["ld_snapshot_layer(to pinned host)"] = {
+            "ms": ms, "bytes": nb, "GBps": nb / (ms * 1e-3) / 1e9,
+            "note": "one 131 M-element layer copied by the same kernel into page-locked host memory: bound by the "
+                    "host link; not part of `value`"}
     if not share:
         print(json.dumps({"calls": calls}), flush=True)
         return

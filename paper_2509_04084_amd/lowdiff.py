@@ -150,11 +150,22 @@ def ld_compress_topk(grad: torch.Tensor, residual: torch.Tensor, seg_off, seg_k,
     return out_idx, out_val
 
 
+def _dev_or_pinned(t: torch.Tensor, dtype, name: str) -> ctypes.c_void_p:
+    """Device tensor, or a pinned host tensor (page-locked memory is mapped into the GPU's address space)."""
+    if not t.is_cuda:
+        if not t.is_pinned() or t.dtype != dtype or not t.is_contiguous():
+            raise TypeError(f"{name}: expected a contiguous {dtype} tensor on the GPU or in pinned host memory")
+        return ctypes.c_void_p(t.data_ptr())
+    return _dev(t, dtype, name)
+
+
 def ld_snapshot_layer(grad_bf16: torch.Tensor, snap_bf16: torch.Tensor, stream=None) -> None:
+    """Copies one layer's gradient into `snap_bf16`: a device tensor, or a pinned host tensor (the
+    paper's device-to-host snapshot; the copy then runs at the host link's speed)."""
     if grad_bf16.numel() != snap_bf16.numel():
         raise ValueError("snapshot source and destination differ in size")
     st = load().ld_snapshot_layer(_dev(grad_bf16, torch.bfloat16, "grad_bf16"),
-                                  _dev(snap_bf16, torch.bfloat16, "snap_bf16"),
+                                  _dev_or_pinned(snap_bf16, torch.bfloat16, "snap_bf16"),
                                   grad_bf16.numel(), _stream(stream))
     _check("ld_snapshot_layer", st)
 
@@ -164,7 +175,7 @@ def ld_snapshot_layers(srcs: Sequence[torch.Tensor], dsts: Sequence[torch.Tensor
     if len(dsts) != n:
         raise ValueError("srcs and dsts differ in length")
     sp = (ctypes.c_void_p * max(n, 1))(*[_dev(t, torch.bfloat16, "src").value or 0 for t in srcs])
-    dp = (ctypes.c_void_p * max(n, 1))(*[_dev(t, torch.bfloat16, "dst").value or 0 for t in dsts])
+    dp = (ctypes.c_void_p * max(n, 1))(*[_dev_or_pinned(t, torch.bfloat16, "dst").value or 0 for t in dsts])
     for a, b in zip(srcs, dsts):
         if a.numel() != b.numel():
             raise ValueError("snapshot source and destination differ in size")

@@ -441,3 +441,20 @@ def test_combine_of_compressed_diffs_and_truncated_output():
     assert int(cnt.item()) == len(oi)
     np.testing.assert_array_equal(out_i[:cap].cpu().numpy(), oi[:cap])
     assert bool((out_i[cap:] == -1).all())
+
+
+def test_snapshot_into_pinned_host_memory():
+    # the paper's snapshot leaves the GPU: the same entry points with a page-locked host destination
+    n = (1 << 22) + 5
+    src = torch.randint(-32768, 32767, (n,), dtype=torch.int16, device=DEV).view(torch.bfloat16)
+    dst = torch.zeros(n, dtype=torch.bfloat16).pin_memory()
+    ld.ld_snapshot_layer(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(dst.view(torch.int16), src.cpu().view(torch.int16))
+    sizes = [1, 4096, 70001, 1 << 20]
+    srcs = [torch.randint(-32768, 32767, (k,), dtype=torch.int16, device=DEV).view(torch.bfloat16) for k in sizes]
+    dsts = [torch.zeros(k, dtype=torch.bfloat16).pin_memory() for k in sizes]
+    ld.ld_snapshot_layers(srcs, dsts)
+    torch.cuda.synchronize()
+    for a, b in zip(srcs, dsts):
+        assert torch.equal(b.view(torch.int16), a.cpu().view(torch.int16))
