@@ -64,6 +64,7 @@ constexpr int kShift1 = 20, kShift2 = 9;          // radix digits: [30:20] [19:9
 constexpr int kPrepThreads = LD_PREP_THREADS;
 constexpr int kSample = 16384;                        // sampled elements per segment
 constexpr int kSampleItems = kSample / kPrepThreads;
+static_assert(kSampleItems <= 32 && kSampleItems % 8 == 0, "valid mask is 32 bits; loads go in batches of 8");
 constexpr int kSampleRuns = kSample / LD_WAVE;        // as 256 runs of 64 consecutive elements
 constexpr float kSampleZ = 6.5f;                  // safety margin of the rank estimate, in sigmas
 constexpr int kGatherBase = 4096;                 // gather list of a segment: kGatherBase + n_s / kGatherPer keys
@@ -377,21 +378,35 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
         const bool whole = ns <= kSample;
         const int lane = threadIdx.x & 63;
         const int64_t stride = ns / kSampleRuns;
+        if (whole) {
 #pragma unroll
-        for (int i = 0; i < kSampleItems; ++i) {
-            int64_t e;
-            if (whole) {
-                e = off + i * kPrepThreads + threadIdx.x;
-            } else {
-                const int run = i * (kPrepThreads / LD_WAVE) + (threadIdx.x >> 6);
-                const int64_t jitter = __umulhi(hash32(static_cast<uint32_t>(run) * 2654435761u + static_cast<uint32_t>(s)),
-                                                static_cast<uint32_t>(stride - LD_WAVE + 1));
-                e = off + run * stride + jitter + lane;
+            for (int i = 0; i < kSampleItems; ++i) {
+                const int64_t e = off + i * kPrepThreads + threadIdx.x;
+                key[i] = 0;
+                if (e < end) {
+                    key[i] = ld_key(__fadd_rn(r[e], g[e]));
+                    valid |= 1u << i;
+                }
             }
-            key[i] = 0;
-            if (e < end) {
-                key[i] = ld_key(__fadd_rn(r[e], g[e]));
-                valid |= 1u << i;
+        } else {
+            // every run lies inside the segment: no bounds checks, and the loads of kLoadBatch
+            // items are issued together (one memory round trip per batch, not per item)
+            constexpr int kLoadBatch = 8;
+            valid = 0xFFFFFFFFu >> (32 - kSampleItems);
+#pragma unroll
+            for (int i0 = 0; i0 < kSampleItems; i0 += kLoadBatch) {
+                float rv[kLoadBatch], gv[kLoadBatch];
+#pragma unroll
+                for (int i = 0; i < kLoadBatch; ++i) {
+                    const int run = (i0 + i) * (kPrepThreads / LD_WAVE) + (threadIdx.x >> 6);
+                    const int64_t jitter = __umulhi(hash32(static_cast<uint32_t>(run) * 2654435761u + static_cast<uint32_t>(s)),
+                                                    static_cast<uint32_t>(stride - LD_WAVE + 1));
+                    const int64_t e = off + run * stride + jitter + lane;
+                    rv[i] = r[e];
+                    gv[i] = g[e];
+                }
+#pragma unroll
+                for (int i = 0; i < kLoadBatch; ++i) key[i0 + i] = ld_key(__fadd_rn(rv[i], gv[i]));
             }
         }
         // Sample ranks (1 = largest). The selected keys are rounded down to 2^kShift2, which only
