@@ -329,7 +329,7 @@ extern "C" ld_status ld_combine_sparse(const int32_t* const* idx, const float* c
     }
     const int32_t nchunk = chunks(n);
     const dim3 grid(static_cast<uint32_t>((nsub + 7) / 8 * 8)), wave(LD_WAVE);
-    k_chunks<<<dim3((nchunk + 1 + 255) / 256, N), dim3(256), 0, s>>>(tb, n, nchunk, ctab);
+    launch_chunks(tb, N, n, nchunk, ctab, s);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     k_combine_count<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts);
     k_combine_groups<<<dim3(ngrp), dim3(256), 0, s>>>(counts, nsub, gsum);

@@ -210,7 +210,7 @@ extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t
             tb.val[t] = live ? val[g0 + t] : nullptr;
             tb.K[t] = live ? static_cast<int32_t>(K[g0 + t]) : 0;
         }
-        k_chunks<<<dim3((nchunk + 1 + 255) / 256, gw), dim3(256), 0, s>>>(tb, n, nchunk, ctab);
+        launch_chunks(tb, gw, n, nchunk, ctab, s);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
         k_merge_sweep<<<dim3((nsub + 7) / 8 * 8), dim3(LD_WAVE), 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;

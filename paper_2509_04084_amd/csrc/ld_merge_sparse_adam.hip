@@ -222,7 +222,7 @@ extern "C" ld_status ld_merge_sparse_adam(float* w, float* m, float* v, int64_t 
         }
         LdAdamSteps a;
         ld_fill_adam_steps(a, gw, step0 + g0, lr, beta1, beta2, eps);
-        k_chunks<<<dim3((nchunk + 1 + 255) / 256, gw), dim3(256), 0, s>>>(tb, n, nchunk, ctab);
+        launch_chunks(tb, gw, n, nchunk, ctab, s);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
         k_sparse_adam<<<dim3((nsub + 7) / 8 * 8), dim3(LD_WAVE), 0, s>>>(w, m, v, n, nchunk, tb, gw, a, ctab);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;

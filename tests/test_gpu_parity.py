@@ -155,6 +155,39 @@ def test_merge_ragged_and_dense_windows(n, W, dens):
         np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref), err_msg=f"strategy {strategy}")
 
 
+def test_merge_uneven_diffs_across_many_chunks():
+    # Record positions are looked up per 49152-element chunk from guesses that assume evenly
+    # spread records; these diffs are anything but (dense runs between long gaps, everything
+    # in the last percent, only the first half, one record), the window spans several
+    # workgroups of the lookup kernel, and two index arrays start at addresses that are
+    # only 4-byte aligned.
+    n = 60_000_003
+    rs = np.random.RandomState(7)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    starts = np.sort(rs.choice(n - 6000, 120, replace=False)).astype(np.int64)
+    runs = np.unique(np.concatenate([np.arange(s0, s0 + 5000) for s0 in starts]))
+    idxs = [runs.astype(np.int32),
+            (n - 600_000 + np.sort(rs.choice(600_000, 400_000, replace=False))).astype(np.int32),
+            np.sort(rs.choice(n, 600_000, replace=False)).astype(np.int32),
+            np.arange(0, n // 2, 64, dtype=np.int32),
+            np.array([n - 1], np.int32),
+            np.unique(np.concatenate([np.arange(0, 40_000), np.arange(n - 40_000, n)])).astype(np.int32)]
+    vals = [rs.standard_normal(i.size).astype(np.float32) for i in idxs]
+    ref = oracle.merge_sparse(w0, idxs, vals, 0.1)
+
+    def shifted(a, shift):  # device copy whose first element sits `shift` elements into an allocation
+        buf = torch.empty(a.size + shift, dtype=torch.from_numpy(a[:1]).dtype, device=DEV)
+        buf[shift:].copy_(torch.from_numpy(a))
+        return buf[shift:]
+
+    gi = [shifted(i, (1, 0, 3, 0, 0, 2)[t]) for t, i in enumerate(idxs)]
+    gv = [shifted(v, (0, 0, 1, 0, 0, 3)[t]) for t, v in enumerate(vals)]
+    w = to_gpu(w0)
+    ld.ld_merge_sparse(w, gi, gv, 0.1, strategy=ld.LD_MERGE_SWEEP)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref))
+
+
 def test_merge_order_and_zero_diff():
     # order sensitivity: swapping two diffs changes the fp32 result; the GPU follows list order
     n = 8192
