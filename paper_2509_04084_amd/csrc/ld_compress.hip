@@ -596,9 +596,11 @@ constexpr int kQuads = kTilesPerWave / 4;
 // Lane u < kTilesPerWave: the candidate count of the wave's tile u (k_main writes a
 // count for every tile slot of every group, 0 past the end of a segment). Fetched
 // first, so that it travels together with the group descriptor.
+__device__ __forceinline__ int wave_in_group() { return static_cast<int>(threadIdx.x >> 6) & (kWaves - 1); }
+
 __device__ __forceinline__ uint32_t wave_counts(const Ctx& c, int32_t group) {
     const int lane = ld_lane();
-    const int32_t tile0 = group * kTilesPerGroup + static_cast<int>(threadIdx.x >> 6) * kTilesPerWave;
+    const int32_t tile0 = group * kTilesPerGroup + wave_in_group() * kTilesPerWave;
     return lane < kTilesPerWave ? c.cnt[tile0 + lane] : 0u;
 }
 
@@ -654,7 +656,7 @@ __device__ __forceinline__ void slow_tiles(const Ctx& c, const float* __restrict
                                            int32_t group, uint32_t mycnt, uint32_t tau, Begin&& begin, Item&& item,
                                            End&& end) {
     const int lane = ld_lane();
-    const int tl0 = static_cast<int>(threadIdx.x >> 6) * kTilesPerWave;
+    const int tl0 = wave_in_group() * kTilesPerWave;
     const int32_t tile0 = group * kTilesPerGroup + tl0;
     const int64_t tbase0 = gr.base + static_cast<int64_t>(tl0) * kTile;
     // tiles of the wave that are not served by the fast path
@@ -714,34 +716,59 @@ __device__ __forceinline__ GroupRange seg_range(const Ctx& c, int32_t s) {
     return r;
 }
 
-// Fine-bin histogram of the candidates of one group, added to the segment's.
-__global__ __launch_bounds__(kThreads) void k_hist(const float* __restrict__ r, Ctx c) {
-    __shared__ uint32_t lh[kBins];
-    const uint32_t mycnt = wave_counts(c, blockIdx.x);
-    const GroupRange gr = group_range(c, blockIdx.x);
-    if (gr.k == 0) return;
-    const uint32_t tau = gr.tau, binsh = gr.sh;
-    const int32_t tile0 = blockIdx.x * kTilesPerGroup + static_cast<int>(threadIdx.x >> 6) * kTilesPerWave;
-    for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
-    __syncthreads();
-    Quad Q, N;
-    quad_fetch<false>(c, tile0, mycnt, 0, Q);
-#pragma unroll 1
-    for (int q = 0; q < kQuads; ++q) {
-        quad_fetch<false>(c, tile0, mycnt, q + 1, N);
-#pragma unroll
-        for (int j = 0; j < kPerLane; ++j)
-            if (static_cast<uint32_t>(j) < Q.have) atomicAdd(&lh[fine_bin(ld_key(Q.v[j]), tau, binsh)], 1u);
-        Q = N;
+// Fine-bin histogram of the candidates of kHistGroups consecutive groups (256 threads each),
+// added to their segments'. Updates of one counter from many workgroups queue up behind one
+// another, and the largest segment has hundreds of groups: the groups of a workgroup that
+// belong to the same segment are summed in LDS first and added once.
+constexpr int kHistGroups = 4;
+
+__global__ __launch_bounds__(kHistGroups * kThreads) void k_hist(const float* __restrict__ r, Ctx c) {
+    __shared__ uint32_t lh[kHistGroups][kBins];
+    __shared__ int32_t qseg[kHistGroups];
+    const int q = threadIdx.x / kThreads, tid = threadIdx.x % kThreads;
+    const int32_t group = blockIdx.x * kHistGroups + q;
+    const bool inside = group < c.n_group;
+    uint32_t mycnt = 0;
+    GroupRange gr;
+    gr.k = 0;
+    if (inside) {
+        mycnt = wave_counts(c, group);
+        gr = group_range(c, group);
     }
-    slow_tiles<false>(
-        c, r, gr, blockIdx.x, mycnt, tau, [](int) {},
-        [&](bool have, float v, uint32_t, bool) {
-            if (have) atomicAdd(&lh[fine_bin(ld_key(v), tau, binsh)], 1u);
-        },
-        [](int) {});
+    const bool live = inside && gr.k != 0;
+    const uint32_t tau = gr.tau, binsh = gr.sh;
+    const int32_t tile0 = group * kTilesPerGroup + wave_in_group() * kTilesPerWave;
+    for (int b = tid; b < kBins; b += kThreads) lh[q][b] = 0;
+    if (tid == 0) qseg[q] = live ? gr.seg : -1;
     __syncthreads();
-    flush_hist(c.hist + static_cast<int64_t>(gr.seg) * kBins, lh);
+    if (live) {
+        Quad Q, N;
+        quad_fetch<false>(c, tile0, mycnt, 0, Q);
+#pragma unroll 1
+        for (int i = 0; i < kQuads; ++i) {
+            quad_fetch<false>(c, tile0, mycnt, i + 1, N);
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j)
+                if (static_cast<uint32_t>(j) < Q.have) atomicAdd(&lh[q][fine_bin(ld_key(Q.v[j]), tau, binsh)], 1u);
+            Q = N;
+        }
+        slow_tiles<false>(
+            c, r, gr, group, mycnt, tau, [](int) {},
+            [&](bool have, float v, uint32_t, bool) {
+                if (have) atomicAdd(&lh[q][fine_bin(ld_key(v), tau, binsh)], 1u);
+            },
+            [](int) {});
+    }
+    __syncthreads();
+    if (!live || (q > 0 && qseg[q - 1] == gr.seg)) return;  // summed by the first group of the run
+    int run = 1;
+    while (q + run < kHistGroups && qseg[q + run] == gr.seg) ++run;
+    uint32_t* h = c.hist + static_cast<int64_t>(gr.seg) * kBins;
+    for (int b = tid; b < kBins; b += kThreads) {
+        uint32_t x = 0;
+        for (int j = 0; j < run; ++j) x += lh[q + j][b];
+        if (x) atomicAdd(h + b, x);
+    }
 }
 
 // One workgroup per segment: the fine bin that holds the k-th largest key, or
@@ -1372,7 +1399,7 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
     k_main<<<dim3(static_cast<uint32_t>(n_group * kTilesPerGroup)), dim3(kMainWaves * LD_WAVE), 0, st>>>(grad, residual, c);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (K == 0) return LD_OK;
-    k_hist<<<grid, block, 0, st>>>(residual, c);
+    k_hist<<<dim3(static_cast<uint32_t>((n_group + kHistGroups - 1) / kHistGroups)), dim3(kHistGroups * kThreads), 0, st>>>(residual, c);
     k_bin<<<sgrid, block, 0, st>>>(c);
     k_gather<<<grid, block, 0, st>>>(residual, c);
     k_select<<<sgrid, block, 0, st>>>(c);
