@@ -94,11 +94,17 @@ const char* ld_status_string(ld_status s);
  *   out_val    dev  [K] fp32
  *   workspace  dev, 256-byte aligned, at least ld_compress_topk_workspace()
  *              bytes; contents on entry are irrelevant, contents on exit are
- *              unspecified
+ *              unspecified. That minimum serves densities seg_k[s]/n_s up to
+ *              about 3 % at full speed; the results are the same at any
+ *              density, but denser calls run faster with the
+ *              ld_compress_topk_workspace_for() size of their seg_k (the call
+ *              uses as much of a larger workspace as its densities ask for)
  * Errors: LD_ERR_NULL, LD_ERR_RANGE (bad table, n > 2^31-1), LD_ERR_ALIGN,
  * LD_ERR_WORKSPACE, LD_ERR_HIP.
  */
 size_t    ld_compress_topk_workspace(int32_t n_seg, const int64_t* seg_off /* host */);
+size_t    ld_compress_topk_workspace_for(int32_t n_seg, const int64_t* seg_off /* host */,
+                                         const int32_t* seg_k /* host */);
 ld_status ld_compress_topk(const float* grad, float* residual,
                            const int64_t* seg_off, const int32_t* seg_k, int32_t n_seg,
                            int32_t* out_idx, float* out_val,

@@ -52,7 +52,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / LD_WAVE;
 constexpr int kTile = 4096;                       // elements per k_main workgroup
-constexpr int kSlot = 256;                        // candidate slots per tile (6.25 %)
+constexpr int kSlotMin = 256;                     // candidate slots per tile: 256 (6.25 % of a tile) serves
+constexpr int kSlotMax = 2048;                    // densities up to ~3 %; denser calls get more (multiples of 64)
 constexpr int kTilesPerGroup = 64;
 constexpr int kGroup = kTile * kTilesPerGroup;    // 262144 elements per small-pass workgroup
 constexpr int kBins = 2048;
@@ -114,8 +115,8 @@ struct Ctx {
     SegState* state;        // [n_seg]
     uint32_t* hist;         // [n_seg][kBins]
     uint32_t* cnt;          // [n_group * 64] candidates stored per tile, or kOverflow
-    float* cval;            // [n_group * 64][kSlot]
-    uint16_t* cidx;         // [n_group * 64][kSlot] element offset inside the tile
+    float* cval;            // [n_group * 64][slot]
+    uint16_t* cidx;         // [n_group * 64][slot] element offset inside the tile
     uint32_t* tile_gt;      // [n_group * 64] keys above T
     uint32_t* tile_eq;      // [n_group * 64] keys equal to T
     uint32_t* group_gt;     // [n_group] sums over the group -> records emitted before the group
@@ -126,6 +127,7 @@ struct Ctx {
     uint32_t* fail_count;   // [1]
     int32_t n_seg;
     int32_t n_group;
+    int32_t slot;           // candidates a tile can store (kSlotMin .. kSlotMax, multiple of 64)
 };
 
 struct UploadBatch {
@@ -538,7 +540,7 @@ __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __re
             btot += x;
         }
     }
-    const bool fits = btot <= kSlot;  // else: the residual keeps r + g everywhere, the slot stays unused
+    const bool fits = btot <= static_cast<uint32_t>(c.slot);  // else: the residual keeps r + g everywhere, the slot stays unused
     if (threadIdx.x == 0) c.cnt[tile] = fits ? btot : kOverflow;
     // residual: +0 where the guessed threshold selects, r + g elsewhere
 #pragma unroll
@@ -552,8 +554,8 @@ __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __re
             store4(r, t + (j * LD_WAVE + lane) * 4, mask[j], x);
     }
     if (!fits || total == 0) return;
-    float* sv = c.cval + static_cast<int64_t>(tile) * kSlot;
-    uint16_t* si = c.cidx + static_cast<int64_t>(tile) * kSlot;
+    float* sv = c.cval + static_cast<int64_t>(tile) * c.slot;
+    uint16_t* si = c.cidx + static_cast<int64_t>(tile) * c.slot;
 #pragma unroll
     for (int j = 0; j < kMainRows; ++j) {
         if (flag[j] == 0) continue;
@@ -574,12 +576,13 @@ __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __re
 //
 // A wave of a small pass owns kTilesPerWave consecutive tiles of its group.
 //
-// Fast path, for tiles with at most kFast stored candidates (nearly all of them):
-// four tiles at a time, one per row of 16 lanes. A lane holds 8 consecutive
-// candidates of its row's tile (two 16-byte loads of values, one of in-tile
-// offsets), so one trip through the loop body serves four tiles, and per-tile sums
-// and prefixes are 16-lane row operations. These passes are bound by instruction
-// issue, not by memory: the body is kept small and rolled.
+// Fast path, for tiles with at most ROW * 8 stored candidates (nearly all of them):
+// 64 / ROW tiles at a time, one per row of ROW lanes (four tiles of up to 128 at the
+// usual 1 % density). A lane holds 8 consecutive candidates of its row's tile (two
+// 16-byte loads of values, one of in-tile offsets), so one trip through the loop body
+// serves several tiles, and per-tile sums and prefixes are row operations. These
+// passes are bound by instruction issue, not by memory: the body is kept small and
+// rolled.
 //
 // Slow path (slow_tiles), for tiles with more stored candidates and for tiles whose
 // slot overflowed (read back from the residual, which then holds r + g unzeroed,
@@ -588,34 +591,42 @@ __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __re
 // lanes together; `local` is the element's offset inside the tile, `stored` tells
 // that the candidate comes from the slot); then end(u).
 constexpr int kTilesPerWave = kTilesPerGroup / kWaves;
-constexpr int kRow = 16;                      // lanes per tile in the fast path
 constexpr int kPerLane = 8;                   // candidates per lane
-constexpr uint32_t kFast = kRow * kPerLane;   // 128
-constexpr int kQuads = kTilesPerWave / 4;
+
+// Shape of the fast path: ROW lanes per tile (16, 32 or 64, chosen per call from the densities),
+// so a trip serves 64 / ROW tiles of at most ROW * 8 candidates each.
+template <int ROW>
+struct Rows {
+    static constexpr int kTiles = LD_WAVE / ROW;                 // tiles per trip
+    static constexpr uint32_t kFast = ROW * kPerLane;            // candidates a tile may hold
+    static constexpr int kTrips = kTilesPerWave / kTiles;
+};
+
+__device__ __forceinline__ int wave_in_group() { return static_cast<int>(threadIdx.x >> 6) & (kWaves - 1); }
 
 // Lane u < kTilesPerWave: the candidate count of the wave's tile u (k_main writes a
 // count for every tile slot of every group, 0 past the end of a segment). Fetched
 // first, so that it travels together with the group descriptor.
-__device__ __forceinline__ int wave_in_group() { return static_cast<int>(threadIdx.x >> 6) & (kWaves - 1); }
-
 __device__ __forceinline__ uint32_t wave_counts(const Ctx& c, int32_t group) {
     const int lane = ld_lane();
     const int32_t tile0 = group * kTilesPerGroup + wave_in_group() * kTilesPerWave;
     return lane < kTilesPerWave ? c.cnt[tile0 + lane] : 0u;
 }
 
-__device__ __forceinline__ uint32_t row_iscan(uint32_t x) {  // inclusive scan over a row of 16 lanes
+template <int ROW>
+__device__ __forceinline__ uint32_t row_iscan(uint32_t x) {  // inclusive scan over a row of ROW lanes
 #pragma unroll
-    for (int d = 1; d < kRow; d <<= 1) {
-        const uint32_t y = __shfl_up(x, d, kRow);
-        if ((ld_lane() & (kRow - 1)) >= d) x += y;
+    for (int d = 1; d < ROW; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d, ROW);
+        if ((ld_lane() & (ROW - 1)) >= d) x += y;
     }
     return x;
 }
 
+template <int ROW>
 __device__ __forceinline__ uint32_t row_sum(uint32_t x) {
 #pragma unroll
-    for (int d = kRow / 2; d > 0; d >>= 1) x += __shfl_xor(x, d, kRow);
+    for (int d = ROW / 2; d > 0; d >>= 1) x += __shfl_xor(x, d, ROW);
     return x;
 }
 
@@ -623,19 +634,20 @@ struct Quad {
     float v[kPerLane];      // candidate values (entries at or past `have` are stale)
     uint32_t x[kPerLane];   // their offsets inside the tile (IDX only)
     uint32_t have;          // valid entries of this lane: 0..kPerLane
-    uint32_t cn;            // stored count of the row's tile (kOverflow, or > kFast: not served here)
+    uint32_t cn;            // stored count of the row's tile (kOverflow, or > ROW * 8: not served here)
     int u;                  // the row's tile, counted inside the wave
 };
 
-// Fetches the lane's part of quad q (tiles 4q .. 4q+3 of the wave); q >= kQuads fetches nothing.
-template <bool IDX>
+// Fetches the lane's part of trip q (tiles kTiles*q .. of the wave); q >= kTrips fetches nothing.
+template <bool IDX, int ROW>
 __device__ __forceinline__ void quad_fetch(const Ctx& c, int32_t tile0, uint32_t mycnt, int q, Quad& Q) {
+    typedef Rows<ROW> R;
     const int lane = ld_lane();
-    const int u = 4 * (q < kQuads ? q : 0) + (lane >> 4);
+    const int u = R::kTiles * (q < R::kTrips ? q : 0) + lane / ROW;
     const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
-    const uint32_t n = (q < kQuads && cn <= kFast) ? cn : 0u;
-    const uint32_t first = static_cast<uint32_t>(lane & (kRow - 1)) * kPerLane;
-    const int64_t at = static_cast<int64_t>(tile0 + u) * kSlot + first;
+    const uint32_t n = (q < R::kTrips && cn <= R::kFast) ? cn : 0u;
+    const uint32_t first = static_cast<uint32_t>(lane & (ROW - 1)) * kPerLane;
+    const int64_t at = static_cast<int64_t>(tile0 + u) * c.slot + first;
     ld_f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
     ld_u32x4 xi = {0u, 0u, 0u, 0u};
     if (first < n) a = *reinterpret_cast<const ld_f32x4*>(c.cval + at);
@@ -651,7 +663,7 @@ __device__ __forceinline__ void quad_fetch(const Ctx& c, int32_t tile0, uint32_t
     Q.u = u;
 }
 
-template <bool IDX, class Begin, class Item, class End>
+template <bool IDX, int ROW, class Begin, class Item, class End>
 __device__ __forceinline__ void slow_tiles(const Ctx& c, const float* __restrict__ r, const GroupRange& gr,
                                            int32_t group, uint32_t mycnt, uint32_t tau, Begin&& begin, Item&& item,
                                            End&& end) {
@@ -660,14 +672,14 @@ __device__ __forceinline__ void slow_tiles(const Ctx& c, const float* __restrict
     const int32_t tile0 = group * kTilesPerGroup + tl0;
     const int64_t tbase0 = gr.base + static_cast<int64_t>(tl0) * kTile;
     // tiles of the wave that are not served by the fast path
-    uint64_t todo = __ballot(lane < kTilesPerWave && mycnt > kFast);
+    uint64_t todo = __ballot(lane < kTilesPerWave && mycnt > Rows<ROW>::kFast);
     while (todo) {
         const int u = __builtin_ctzll(todo);
         todo &= todo - 1;
         const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
         const bool stored = cn != kOverflow;
         const uint32_t total = stored ? cn : static_cast<uint32_t>(kTile);
-        const int64_t slot = static_cast<int64_t>(tile0 + u) * kSlot;
+        const int64_t slot = static_cast<int64_t>(tile0 + u) * c.slot;
         const int64_t tbase = tbase0 + static_cast<int64_t>(u) * kTile;
         begin(u);
 #pragma unroll 1
@@ -722,6 +734,7 @@ __device__ __forceinline__ GroupRange seg_range(const Ctx& c, int32_t s) {
 // belong to the same segment are summed in LDS first and added once.
 constexpr int kHistGroups = 4;
 
+template <int ROW>
 __global__ __launch_bounds__(kHistGroups * kThreads) void k_hist(const float* __restrict__ r, Ctx c) {
     __shared__ uint32_t lh[kHistGroups][kBins];
     __shared__ int32_t qseg[kHistGroups];
@@ -742,22 +755,34 @@ __global__ __launch_bounds__(kHistGroups * kThreads) void k_hist(const float* __
     if (tid == 0) qseg[q] = live ? gr.seg : -1;
     __syncthreads();
     if (live) {
+        // keys above the binned range all land in the top bin (a third of the candidates, more
+        // at higher densities): counted in a register, added once per wave
+        uint32_t top = 0;
         Quad Q, N;
-        quad_fetch<false>(c, tile0, mycnt, 0, Q);
+        quad_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
-        for (int i = 0; i < kQuads; ++i) {
-            quad_fetch<false>(c, tile0, mycnt, i + 1, N);
+        for (int i = 0; i < Rows<ROW>::kTrips; ++i) {
+            quad_fetch<false, ROW>(c, tile0, mycnt, i + 1, N);
 #pragma unroll
-            for (int j = 0; j < kPerLane; ++j)
-                if (static_cast<uint32_t>(j) < Q.have) atomicAdd(&lh[q][fine_bin(ld_key(Q.v[j]), tau, binsh)], 1u);
+            for (int j = 0; j < kPerLane; ++j) {
+                if (static_cast<uint32_t>(j) < Q.have) {
+                    const uint32_t bin = fine_bin(ld_key(Q.v[j]), tau, binsh);
+                    if (bin == static_cast<uint32_t>(kTopBin)) ++top; else atomicAdd(&lh[q][bin], 1u);
+                }
+            }
             Q = N;
         }
-        slow_tiles<false>(
+        slow_tiles<false, ROW>(
             c, r, gr, group, mycnt, tau, [](int) {},
             [&](bool have, float v, uint32_t, bool) {
-                if (have) atomicAdd(&lh[q][fine_bin(ld_key(v), tau, binsh)], 1u);
+                if (have) {
+                    const uint32_t bin = fine_bin(ld_key(v), tau, binsh);
+                    if (bin == static_cast<uint32_t>(kTopBin)) ++top; else atomicAdd(&lh[q][bin], 1u);
+                }
             },
             [](int) {});
+        top = ld_wave_sum(top);
+        if (ld_lane() == 0 && top) atomicAdd(&lh[q][kTopBin], top);
     }
     __syncthreads();
     if (!live || (q > 0 && qseg[q - 1] == gr.seg)) return;  // summed by the first group of the run
@@ -794,6 +819,7 @@ __global__ __launch_bounds__(kThreads) void k_bin(Ctx c) {
 
 // Per tile: candidates in bins above the threshold bin; the keys inside the bin
 // are gathered per segment.
+template <int ROW>
 __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r, Ctx c) {
     __shared__ uint32_t wsum[kWaves];
     const uint32_t mycnt = wave_counts(c, blockIdx.x);
@@ -809,10 +835,10 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     const int32_t tile0 = blockIdx.x * kTilesPerGroup + w * kTilesPerWave;
     uint32_t part_gt = 0;  // fast path: the first lane of a row sums the row's tiles
     Quad Q, N;
-    quad_fetch<false>(c, tile0, mycnt, 0, Q);
+    quad_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
-    for (int q = 0; q < kQuads; ++q) {
-        quad_fetch<false>(c, tile0, mycnt, q + 1, N);
+    for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
+        quad_fetch<false, ROW>(c, tile0, mycnt, q + 1, N);
         uint32_t cnt = 0, in = 0;
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
@@ -833,8 +859,8 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
                 }
             }
         }
-        cnt = row_sum(cnt);
-        if ((lane & (kRow - 1)) == 0 && Q.cn <= kFast) {
+        cnt = row_sum<ROW>(cnt);
+        if ((lane & (ROW - 1)) == 0 && Q.cn <= Rows<ROW>::kFast) {
             c.tile_gt[tile0 + Q.u] = cnt;
             c.tile_eq[tile0 + Q.u] = 0;
             part_gt += cnt;
@@ -843,7 +869,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     }
     uint32_t slow_gt = 0, gt = 0;
     int32_t tile_of_item = 0;
-    slow_tiles<false>(
+    slow_tiles<false, ROW>(
         c, r, gr, blockIdx.x, mycnt, tau,
         [&](int u) {
             gt = 0;
@@ -972,11 +998,14 @@ __global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
 // stored candidate's key reaches T_est; only where that guess and the selection
 // differ is the residual written again. A segment handed to the full path gets
 // every pre-zeroed position back instead.
+template <int ROW>
 __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_t* __restrict__ out_idx,
                                                    float* __restrict__ out_val, Ctx c) {
     __shared__ uint32_t tile_out[kTilesPerGroup], tile_eqb[kTilesPerGroup];
-    __shared__ int32_t stage_i[kWaves][4 * kFast];
-    __shared__ float stage_v[kWaves][4 * kFast];
+    constexpr int kTiles = Rows<ROW>::kTiles;
+    constexpr uint32_t kFast = Rows<ROW>::kFast;
+    __shared__ int32_t stage_i[kWaves][kTiles * kFast];
+    __shared__ float stage_v[kWaves][kTiles * kFast];
     const uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
     const SegState* st = c.state + gr.seg;
@@ -989,17 +1018,17 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     int64_t tbase = 0;
     Quad Q, N;
     if (st->mode != kModeCand) {
-        quad_fetch<true>(c, tile0, mycnt, 0, Q);
+        quad_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
-        for (int q = 0; q < kQuads; ++q) {
-            quad_fetch<true>(c, tile0, mycnt, q + 1, N);
+        for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
+            quad_fetch<true, ROW>(c, tile0, mycnt, q + 1, N);
             float* rt = r + gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile;
 #pragma unroll
             for (int j = 0; j < kPerLane; ++j)
                 if (static_cast<uint32_t>(j) < Q.have && ld_key(Q.v[j]) >= test) rt[Q.x[j]] = Q.v[j];
             Q = N;
         }
-        slow_tiles<true>(
+        slow_tiles<true, ROW>(
             c, r, gr, blockIdx.x, mycnt, tau,
             [&](int u) { tbase = gr.base + static_cast<int64_t>(tl0 + u) * kTile; },
             [&](bool have, float v, uint32_t local, bool stored) {
@@ -1018,10 +1047,10 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
         tile_eqb[lane] = eq_before;
     }
     __syncthreads();
-    quad_fetch<true>(c, tile0, mycnt, 0, Q);
+    quad_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
-    for (int q = 0; q < kQuads; ++q) {
-        quad_fetch<true>(c, tile0, mycnt, q + 1, N);
+    for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
+        quad_fetch<true, ROW>(c, tile0, mycnt, q + 1, N);
         const uint32_t out_tile = tile_out[tl0 + Q.u], eq_tile = tile_eqb[tl0 + Q.u];
         uint32_t gtm = 0, eqm = 0;
 #pragma unroll
@@ -1031,8 +1060,8 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
             gtm |= static_cast<uint32_t>(valid && key > T) << j;
             eqm |= static_cast<uint32_t>(valid && key == T) << j;
         }
-        const uint32_t mine = __popc(gtm) | (__popc(eqm) << 16);  // a tile holds at most 128 here
-        const uint32_t before = row_iscan(mine) - mine;
+        const uint32_t mine = __popc(gtm) | (__popc(eqm) << 16);  // a tile holds at most 512 here
+        const uint32_t before = row_iscan<ROW>(mine) - mine;
         uint32_t gt_before = before & 0xFFFFu;
         uint32_t eq_rank = eq_tile + (before >> 16);
         float* rt = r + gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile;
@@ -1040,8 +1069,8 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
         // the records of a row's tile are staged in LDS at their rank inside the tile and then
         // written out as contiguous runs (stores of single records from scattered lanes cost
         // three times as much)
-        int32_t* si = stage_i[w] + (lane >> 4) * kFast;
-        float* sv = stage_v[w] + (lane >> 4) * kFast;
+        int32_t* si = stage_i[w] + (lane / ROW) * kFast;
+        float* sv = stage_v[w] + (lane / ROW) * kFast;
         uint32_t rank = 0;
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
@@ -1060,9 +1089,9 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
         rank = gt_before + (umin(eq_rank, m) - umin(eq_tile, m));  // in a row's last lane: records of the tile
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 #pragma unroll
-        for (int row = 0; row < 4; ++row) {
-            const uint32_t cnt = static_cast<uint32_t>(__shfl(static_cast<int>(rank), row * kRow + kRow - 1, LD_WAVE));
-            const int64_t o0 = gr.out0 + tile_out[tl0 + 4 * q + row];
+        for (int row = 0; row < kTiles; ++row) {
+            const uint32_t cnt = static_cast<uint32_t>(__shfl(static_cast<int>(rank), row * ROW + ROW - 1, LD_WAVE));
+            const int64_t o0 = gr.out0 + tile_out[tl0 + kTiles * q + row];
             for (uint32_t i = lane; i < cnt; i += LD_WAVE) {
                 out_idx[o0 + i] = stage_i[w][row * kFast + i];
                 out_val[o0 + i] = stage_v[w][row * kFast + i];
@@ -1073,7 +1102,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     }
     uint32_t run_out = 0;  // records of the segment emitted before this point
     uint32_t run_eq = 0;   // ties seen before this point
-    slow_tiles<true>(
+    slow_tiles<true, ROW>(
         c, r, gr, blockIdx.x, mycnt, tau,
         [&](int u) {
             run_out = tile_out[tl0 + u];
@@ -1274,7 +1303,7 @@ struct Layout {
         fail_groups, fail_count, total;
 };
 
-Layout layout(int32_t n_seg, int64_t n_group) {
+Layout layout(int32_t n_seg, int64_t n_group, int32_t slot) {
     Layout L;
     size_t o = 0;
     const size_t ns = static_cast<size_t>(n_seg), ng = static_cast<size_t>(n_group), nt = ng * kTilesPerGroup;
@@ -1284,8 +1313,6 @@ Layout layout(int32_t n_seg, int64_t n_group) {
     L.state = take(sizeof(SegState) * ns);
     L.hist = take(sizeof(uint32_t) * kBins * ns);
     L.cnt = take(4 * nt);
-    L.cval = take(4 * nt * kSlot);
-    L.cidx = take(2 * nt * kSlot);
     L.tile_gt = take(4 * nt);
     L.tile_eq = take(4 * nt);
     L.group_gt = take(4 * ng);
@@ -1295,6 +1322,8 @@ Layout layout(int32_t n_seg, int64_t n_group) {
     L.gtile = take(4 * gather_entries);
     L.fail_groups = take(4 * ng);
     L.fail_count = take(4);
+    L.cval = take(4 * nt * static_cast<size_t>(slot));  // the two arrays whose size depends on `slot` come last
+    L.cidx = take(2 * nt * static_cast<size_t>(slot));
     L.total = o;
     return L;
 }
@@ -1311,12 +1340,43 @@ int64_t count_groups(int32_t n_seg, const int64_t* seg_off) {
     return total;
 }
 
+// Slot size that holds the candidates of a tile in all but a few tiles: the candidate threshold
+// of k_prep sits at sample rank x = a + z*sqrt(x) (a = k * kSample / n_s expected hits), i.e. a
+// fraction x / kSample of the elements are candidates, plus five sigmas of a tile's own count.
+// Taken over the segments of at least 16 tiles (the tiles of smaller ones may overflow into the
+// residual re-read: there are few of them).
+int32_t wanted_slot(int32_t n_seg, const int64_t* seg_off, const int32_t* seg_k, int32_t* per_tile = nullptr) {
+    double most = 0.0;
+    for (int32_t s = 0; s < n_seg; ++s) {
+        const int64_t ns = seg_off[s + 1] - seg_off[s];
+        if (ns < 16 * kTile || seg_k[s] <= 0) continue;
+        const double a = static_cast<double>(seg_k[s]) * kSample / static_cast<double>(ns);
+        const double sq = 0.5 * (kSampleZ + sqrt(kSampleZ * kSampleZ + 4.0 * a));
+        const double x = sq * sq + 2.0;
+        if (x >= kSample) continue;  // no estimate for this segment: every element is a candidate
+        const double per_tile = x * kTile / kSample;
+        const double need = per_tile + 5.0 * sqrt(per_tile) + 8.0;
+        if (need > most) most = need;
+    }
+    if (per_tile) *per_tile = static_cast<int32_t>(most);
+    int64_t slot = (static_cast<int64_t>(most) + 63) / 64 * 64;
+    if (slot < kSlotMin) slot = kSlotMin;
+    if (slot > kSlotMax) slot = kSlotMax;
+    return static_cast<int32_t>(slot);
+}
+
 }  // namespace
 
 extern "C" size_t ld_compress_topk_workspace(int32_t n_seg, const int64_t* seg_off) {
     const int64_t n_group = count_groups(n_seg, seg_off);
     if (n_group < 0) return 0;
-    return layout(n_seg, n_group).total;
+    return layout(n_seg, n_group, kSlotMin).total;
+}
+
+extern "C" size_t ld_compress_topk_workspace_for(int32_t n_seg, const int64_t* seg_off, const int32_t* seg_k) {
+    const int64_t n_group = count_groups(n_seg, seg_off);
+    if (n_group < 0 || (n_seg > 0 && !seg_k)) return 0;
+    return layout(n_seg, n_group, wanted_slot(n_seg, seg_off, seg_k)).total;
 }
 
 extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residual, const int64_t* seg_off,
@@ -1341,8 +1401,13 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
     if (!ld_aligned(grad, 16) || !ld_aligned(residual, 16) || !ld_aligned(out_idx, 4) ||
         !ld_aligned(out_val, 4))
         return LD_ERR_ALIGN;
-    const Layout L = layout(n_seg, n_group);
-    if (!workspace || !ld_aligned(workspace, 256) || workspace_bytes < L.total) return LD_ERR_WORKSPACE;
+    if (!workspace || !ld_aligned(workspace, 256) || workspace_bytes < layout(n_seg, n_group, kSlotMin).total)
+        return LD_ERR_WORKSPACE;
+    // the largest slot, up to the one this call's densities ask for, that the workspace holds
+    int32_t per_tile = 0;
+    int32_t slot = wanted_slot(n_seg, seg_off, seg_k, &per_tile);
+    while (slot > kSlotMin && layout(n_seg, n_group, slot).total > workspace_bytes) slot -= 64;
+    const Layout L = layout(n_seg, n_group, slot);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
@@ -1364,6 +1429,7 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
     c.fail_count = reinterpret_cast<uint32_t*>(ws + L.fail_count);
     c.n_seg = n_seg;
     c.n_group = static_cast<int32_t>(n_group);
+    c.slot = slot;
 
     // segment table travels as kernel arguments, kSegPerLaunch segments per launch
     {
@@ -1399,11 +1465,20 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
     k_main<<<dim3(static_cast<uint32_t>(n_group * kTilesPerGroup)), dim3(kMainWaves * LD_WAVE), 0, st>>>(grad, residual, c);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (K == 0) return LD_OK;
-    k_hist<<<dim3(static_cast<uint32_t>((n_group + kHistGroups - 1) / kHistGroups)), dim3(kHistGroups * kThreads), 0, st>>>(residual, c);
+    const dim3 hgrid(static_cast<uint32_t>((n_group + kHistGroups - 1) / kHistGroups)), hblock(kHistGroups * kThreads);
+    // lanes per tile in the candidate passes: enough for the candidates a tile is expected to hold
+    const int row = per_tile <= 128 ? 16 : (per_tile <= 256 ? 32 : 64);
+    if (row == 16) k_hist<16><<<hgrid, hblock, 0, st>>>(residual, c);
+    else if (row == 32) k_hist<32><<<hgrid, hblock, 0, st>>>(residual, c);
+    else k_hist<64><<<hgrid, hblock, 0, st>>>(residual, c);
     k_bin<<<sgrid, block, 0, st>>>(c);
-    k_gather<<<grid, block, 0, st>>>(residual, c);
+    if (row == 16) k_gather<16><<<grid, block, 0, st>>>(residual, c);
+    else if (row == 32) k_gather<32><<<grid, block, 0, st>>>(residual, c);
+    else k_gather<64><<<grid, block, 0, st>>>(residual, c);
     k_select<<<sgrid, block, 0, st>>>(c);
-    k_emit<<<grid, block, 0, st>>>(residual, out_idx, out_val, c);
+    if (row == 16) k_emit<16><<<grid, block, 0, st>>>(residual, out_idx, out_val, c);
+    else if (row == 32) k_emit<32><<<grid, block, 0, st>>>(residual, out_idx, out_val, c);
+    else k_emit<64><<<grid, block, 0, st>>>(residual, out_idx, out_val, c);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     // segments handed to the full path (normally none: these exit at once)
     const dim3 fgrid(static_cast<uint32_t>(n_group < kFullGrid ? n_group : kFullGrid));

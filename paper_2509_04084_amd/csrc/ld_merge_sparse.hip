@@ -183,8 +183,10 @@ extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t
     int64_t total = 0;
     for (int32_t t = 0; t < W; ++t) total += K[t];
     if (total == 0) return LD_OK;
+    // measured on 1.56 G elements: a scattered record costs 46 ps, the sweep 1.35 ps per element of w
+    // plus little per record: they meet where the window holds n / 34 records
     if (strategy == LD_MERGE_AUTO)
-        strategy = (total * 16 >= n) ? LD_MERGE_SWEEP : LD_MERGE_SCATTER;
+        strategy = (total * 32 >= n) ? LD_MERGE_SWEEP : LD_MERGE_SCATTER;
 
     if (strategy == LD_MERGE_SCATTER) {
         for (int32_t t = 0; t < W; ++t) {

@@ -48,6 +48,8 @@ def load() -> ctypes.CDLL:
     lib.ld_status_string.restype = ctypes.c_char_p
     lib.ld_compress_topk_workspace.argtypes = [i32, vp]
     lib.ld_compress_topk_workspace.restype = sz
+    lib.ld_compress_topk_workspace_for.argtypes = [i32, vp, vp]
+    lib.ld_compress_topk_workspace_for.restype = sz
     lib.ld_compress_topk.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.ld_compress_topk.restype = i32
     lib.ld_compress_topk_strategy.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, sz, vp, i32]
@@ -114,9 +116,15 @@ def _hp(a: np.ndarray) -> ctypes.c_void_p:
     return ctypes.c_void_p(a.ctypes.data)
 
 
-def ld_compress_topk_workspace(seg_off) -> int:
+def ld_compress_topk_workspace(seg_off, seg_k=None) -> int:
+    """Workspace bytes: the minimum, or with `seg_k` the size that keeps calls of that density fast."""
     seg_off = _host(seg_off, np.int64)
-    return int(load().ld_compress_topk_workspace(seg_off.shape[0] - 1, _hp(seg_off)))
+    if seg_k is None:
+        return int(load().ld_compress_topk_workspace(seg_off.shape[0] - 1, _hp(seg_off)))
+    seg_k = _host(seg_k, np.int32)
+    if seg_k.shape[0] != seg_off.shape[0] - 1:
+        raise ValueError("seg_k must have one entry per segment")
+    return int(load().ld_compress_topk_workspace_for(seg_off.shape[0] - 1, _hp(seg_off), _hp(seg_k)))
 
 
 def ld_compress_topk(grad: torch.Tensor, residual: torch.Tensor, seg_off, seg_k,
@@ -139,7 +147,7 @@ def ld_compress_topk(grad: torch.Tensor, residual: torch.Tensor, seg_off, seg_k,
     if out_idx.numel() < K or out_val.numel() < K:
         raise ValueError("output buffers smaller than sum(seg_k)")
     if workspace is None:
-        workspace = torch.empty(max(1, int(lib.ld_compress_topk_workspace(n_seg, _hp(seg_off)))),
+        workspace = torch.empty(max(1, int(lib.ld_compress_topk_workspace_for(n_seg, _hp(seg_off), _hp(seg_k)))),
                                 dtype=torch.uint8, device=grad.device)
     st = lib.ld_compress_topk_strategy(
         _dev(grad, torch.float32, "grad"), _dev(residual, torch.float32, "residual"),

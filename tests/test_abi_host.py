@@ -65,6 +65,26 @@ def test_compress_argument_errors():
     assert lib.ld_compress_topk_workspace(2, _p(np.array([0, 300, 100], np.int64))) == 0
 
 
+def test_compress_workspace_for_density():
+    # the density-aware query never asks for less than the minimum, equals it at the usual 1 %,
+    # grows with the density of the large segments only, and is 0 for a malformed table
+    off = np.array([0, 1000, 2_000_000, 2_100_000], np.int64)
+    base = ld.ld_compress_topk_workspace(off)
+    sizes = np.diff(off)
+
+    def at(frac):
+        return ld.ld_compress_topk_workspace(off, np.maximum(1, (sizes * frac).astype(np.int32)))
+
+    assert at(0.001) == base and at(0.01) == base
+    assert base < at(0.05) < at(0.10) < at(0.25)
+    dense_small = np.array([1000, 20000, 1000], np.int32)   # only the 1000-element segment is dense
+    assert ld.ld_compress_topk_workspace(off, dense_small) == base
+    lib = ld.load()
+    assert lib.ld_compress_topk_workspace_for(2, _p(np.array([0, 300, 100], np.int64)),
+                                              _p(np.array([1, 1], np.int32))) == 0
+    assert lib.ld_compress_topk_workspace_for(2, _p(off), ctypes.c_void_p(0)) == 0
+
+
 def test_merge_sparse_argument_errors():
     lib = ld.load()
     V = ctypes.c_void_p

@@ -76,6 +76,29 @@ def test_compress_adversarial(n):
             check_compress(g, r, off, np.array(k, np.int32), tag=f"{name} k={k}")
 
 
+@pytest.mark.parametrize("rho", [(2, 100), (3, 100), (5, 100), (75, 1000), (10, 100), (25, 100)])
+def test_compress_density_range(rho):
+    # Densities of the paper's Exp. 10 range and beyond: the candidate passes change shape with
+    # the density (lanes per tile, slot size). Once with the workspace the binding sizes for
+    # the call's seg_k, once with the minimum one (the tiles then overflow their slots).
+    sizes = [300000, 70000, 1200000, 4097, 65536]
+    off = synth.seg_offsets(sizes)
+    k = synth.seg_topk(sizes, *rho)
+    rs = np.random.RandomState(rho[0])
+    n = int(off[-1])
+    g = (rs.standard_t(3, n) * 1e-3).astype(np.float32)
+    r = (rs.standard_t(3, n) * 3e-4).astype(np.float32)
+    oi, ov, orr = check_compress(g, r, off, k, tag=f"rho={rho}", strategies=(ld.LD_COMPRESS_AUTO,))
+    assert ld.ld_compress_topk_workspace(off, k) >= ld.ld_compress_topk_workspace(off)
+    small = torch.empty(ld.ld_compress_topk_workspace(off), dtype=torch.uint8, device=DEV)
+    r_gpu = to_gpu(r)
+    idx, val = ld.ld_compress_topk(to_gpu(g), r_gpu, off, k, workspace=small)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(idx.cpu().numpy(), oi)
+    np.testing.assert_array_equal(bits(val.cpu().numpy()), bits(ov))
+    np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(orr))
+
+
 def test_compress_resnet50_shape():
     wl = synth.workload("resnet50")
     g = synth.gradient(wl, 0).numpy()
