@@ -37,17 +37,29 @@ __device__ __forceinline__ void apply_record(float* tile, int32_t local, float v
     tile[local] = __fsub_rn(tile[local], p);
 }
 
-// Applies the records of one diff at positions [p, end) that fall into [lo, hi), 64 at a
-// time, up to the first record at or beyond hi.
+// Applies the records of one diff at positions [p, end) that fall into [lo, hi), up to the
+// first record at or beyond hi. kDeep loads of 64 records are in flight together: a dense
+// diff has many such batches per sub-tile, and one at a time would leave the wave waiting
+// for memory once per batch.
+constexpr int kDeep = 8;
+
 __device__ __forceinline__ void apply_from(float* tile, const int32_t* __restrict__ idx,
                                            const float* __restrict__ val, int32_t p, int32_t end,
                                            int32_t lo, int32_t hi, float lr, int lane) {
-    for (; p < end; p += LD_WAVE) {
-        const bool have = p + lane < end;
-        const int32_t i = have ? idx[p + lane] : INT_MAX;
-        const float v = have ? val[p + lane] : 0.0f;
-        if (i >= lo && i < hi) apply_record(tile, i - lo, v, lr);
-        if (__ballot(i >= hi)) break;
+    for (; p < end; p += kDeep * LD_WAVE) {
+        int32_t i[kDeep];
+        float v[kDeep];
+#pragma unroll
+        for (int u = 0; u < kDeep; ++u) {
+            const int32_t q = p + u * LD_WAVE + lane;
+            const bool have = q < end;
+            i[u] = have ? idx[q] : INT_MAX;
+            v[u] = have ? val[q] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kDeep; ++u)
+            if (i[u] >= lo && i[u] < hi) apply_record(tile, i[u] - lo, v[u], lr);
+        if (__ballot(i[kDeep - 1] >= hi)) break;
     }
 }
 
