@@ -514,3 +514,70 @@ def test_snapshot_into_pinned_host_memory():
     torch.cuda.synchronize()
     for a, b in zip(srcs, dsts):
         assert torch.equal(b.view(torch.int16), a.cpu().view(torch.int16))
+
+
+# ------------------------------------------------------------ graph capture
+
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    # The entry points only enqueue kernels on the caller's stream (no allocation, no copy, no
+    # memset, no synchronisation), so a compress + merge + Adam sequence can be captured once and
+    # replayed. Every replay, with fresh inputs and eager work in between, must give what
+    # the oracle gives.
+    wl = synth.workload("flat1m")
+    off, k = wl.seg_off, wl.seg_k
+    K = int(k.sum())
+    n = wl.n
+    g = torch.zeros(n, device=DEV)
+    r = torch.zeros(n, device=DEV)
+    w = torch.zeros(n, device=DEV)
+    m = torch.zeros(n, device=DEV)
+    v = torch.zeros(n, device=DEV)
+    gb = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    snap = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    oi = torch.empty(K, dtype=torch.int32, device=DEV)
+    ov = torch.empty(K, dtype=torch.float32, device=DEV)
+    ws_c = torch.empty(ld.ld_compress_topk_workspace(off, k), dtype=torch.uint8, device=DEV)
+    ws_m = torch.empty(ld.ld_merge_sparse_workspace(n, [K]), dtype=torch.uint8, device=DEV)
+
+    def sequence():
+        ld.ld_compress_topk(g, r, off, k, oi, ov, ws_c)
+        ld.ld_merge_sparse(w, [oi], [ov], wl.lr, ws_m, strategy=ld.LD_MERGE_SWEEP)
+        ld.ld_snapshot_layer(gb, snap)
+        ld.ld_merge_dense_adam(w, m, v, [snap], 0, 1e-4, **synth.ADAM)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sequence()  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sequence()
+
+    r_host = np.zeros(n, np.float32)
+    for rep in range(3):
+        g_host = synth.gradient(wl, 10 + rep).numpy()
+        w_host = synth.base_weights(n).numpy() * np.float32(1 + rep)
+        gb_t = (synth.gradient(wl, 20 + rep) * 1e-3).to(torch.bfloat16)
+        g.copy_(torch.from_numpy(g_host))
+        r.copy_(torch.from_numpy(r_host))
+        w.copy_(torch.from_numpy(w_host))
+        m.zero_()
+        v.zero_()
+        gb.copy_(gb_t)
+        graph.replay()
+        torch.cuda.synchronize()
+        ei, ev, er = oracle.topk_ef(g_host, r_host, off, k, select=True)
+        np.testing.assert_array_equal(oi.cpu().numpy(), ei, err_msg=f"replay {rep}")
+        np.testing.assert_array_equal(bits(ov.cpu().numpy()), bits(ev), err_msg=f"replay {rep}")
+        np.testing.assert_array_equal(bits(r.cpu().numpy()), bits(er), err_msg=f"replay {rep}")
+        w_merged = oracle.merge_sparse(w_host, [ei], [ev], wl.lr)
+        gbits = gb_t.view(torch.int16).numpy().view(np.uint16)
+        np.testing.assert_array_equal(snap.cpu().view(torch.int16).numpy().view(np.uint16), gbits)
+        zeros = np.zeros(n, np.float32)
+        rw, rm, rv = oracle.adam_replay(w_merged, zeros, zeros, [gbits], 0, 1e-4, **synth.ADAM)
+        check_adam_close((w, m, v), (rw, rm, rv), f"replay {rep}")
+        r_host = er
+        # eager work between the replays, on the same buffers' neighbours
+        torch.randn(1 << 20, device=DEV).sum().item()
