@@ -40,6 +40,9 @@
 //     gather list holds (massive ties), gets its residual restored from the slots
 //     and is handed to the k_full_* kernels: a plain three-level radix select over
 //     the whole segment.
+// The slot size (256 .. 2048 candidates per tile) and the lanes per tile of the candidate
+// passes (16, 32 or 64) are chosen per call from the densities seg_k / n_s, so that calls
+// at 5 or 10 % keep the same structure (the paper varies rho from 0.001 to 0.1, Exp. 10).
 // Per-segment steps run as kernels of their own (a kernel boundary is the only
 // device-wide hand-over the normal path needs); the k_full_* kernels hand over
 // with a ticket counter (device-scope release / acquire).
@@ -630,7 +633,7 @@ __device__ __forceinline__ uint32_t row_sum(uint32_t x) {
     return x;
 }
 
-struct Quad {
+struct Trip {
     float v[kPerLane];      // candidate values (entries at or past `have` are stale)
     uint32_t x[kPerLane];   // their offsets inside the tile (IDX only)
     uint32_t have;          // valid entries of this lane: 0..kPerLane
@@ -640,7 +643,7 @@ struct Quad {
 
 // Fetches the lane's part of trip q (tiles kTiles*q .. of the wave); q >= kTrips fetches nothing.
 template <bool IDX, int ROW>
-__device__ __forceinline__ void quad_fetch(const Ctx& c, int32_t tile0, uint32_t mycnt, int q, Quad& Q) {
+__device__ __forceinline__ void trip_fetch(const Ctx& c, int32_t tile0, uint32_t mycnt, int q, Trip& Q) {
     typedef Rows<ROW> R;
     const int lane = ld_lane();
     const int u = R::kTiles * (q < R::kTrips ? q : 0) + lane / ROW;
@@ -758,11 +761,11 @@ __global__ __launch_bounds__(kHistGroups * kThreads) void k_hist(const float* __
         // keys above the binned range all land in the top bin (a third of the candidates, more
         // at higher densities): counted in a register, added once per wave
         uint32_t top = 0;
-        Quad Q, N;
-        quad_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
+        Trip Q, N;
+        trip_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
         for (int i = 0; i < Rows<ROW>::kTrips; ++i) {
-            quad_fetch<false, ROW>(c, tile0, mycnt, i + 1, N);
+            trip_fetch<false, ROW>(c, tile0, mycnt, i + 1, N);
 #pragma unroll
             for (int j = 0; j < kPerLane; ++j) {
                 if (static_cast<uint32_t>(j) < Q.have) {
@@ -834,11 +837,11 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     const uint32_t gcap = gather_cap(gr.lo, gr.hi);
     const int32_t tile0 = blockIdx.x * kTilesPerGroup + w * kTilesPerWave;
     uint32_t part_gt = 0;  // fast path: the first lane of a row sums the row's tiles
-    Quad Q, N;
-    quad_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
+    Trip Q, N;
+    trip_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
     for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
-        quad_fetch<false, ROW>(c, tile0, mycnt, q + 1, N);
+        trip_fetch<false, ROW>(c, tile0, mycnt, q + 1, N);
         uint32_t cnt = 0, in = 0;
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
@@ -1016,12 +1019,12 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     const int tl0 = w * kTilesPerWave;
     const int32_t tile0 = blockIdx.x * kTilesPerGroup + tl0;
     int64_t tbase = 0;
-    Quad Q, N;
+    Trip Q, N;
     if (st->mode != kModeCand) {
-        quad_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
+        trip_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
         for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
-            quad_fetch<true, ROW>(c, tile0, mycnt, q + 1, N);
+            trip_fetch<true, ROW>(c, tile0, mycnt, q + 1, N);
             float* rt = r + gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile;
 #pragma unroll
             for (int j = 0; j < kPerLane; ++j)
@@ -1047,10 +1050,10 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
         tile_eqb[lane] = eq_before;
     }
     __syncthreads();
-    quad_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
+    trip_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
     for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
-        quad_fetch<true, ROW>(c, tile0, mycnt, q + 1, N);
+        trip_fetch<true, ROW>(c, tile0, mycnt, q + 1, N);
         const uint32_t out_tile = tile_out[tl0 + Q.u], eq_tile = tile_eqb[tl0 + Q.u];
         uint32_t gtm = 0, eqm = 0;
 #pragma unroll
