@@ -405,7 +405,10 @@ def main():
         print(json.dumps({"calls": calls}), flush=True)
         return
     dom = max(share, key=share.get)
-    traffic = measured_traffic(os.path.join(ROOT, "profiles", "hbm_traffic_gpt2xl_llama7b.txt"))
+    # the committed counter summary was taken on the default workloads: it says nothing about others
+    traffic = {}
+    if args.sparse == "gpt2xl" and args.dense == "llama7b":
+        traffic = measured_traffic(os.path.join(ROOT, "profiles", "hbm_traffic_gpt2xl_llama7b.txt"))
     for name, c in calls.items():
         c["traffic_bytes"] = traffic.get(name.split("(")[0])
     roofline = {"bound": "hbm", "kernel": dom, "achieved": calls[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS,
