@@ -225,3 +225,14 @@ def adversarial_cases(n: int, seed: int = 0):
     g = np.sort(np.abs(rs.standard_normal(n))).astype(np.float32)  # winners all at the end
     yield "ascending", g, z.copy()
     yield "descending", g[::-1].copy(), z.copy()
+    # infinities are ordinary keys (the largest); finite residuals keep r + g free of NaN. Enough
+    # of them that some segments select only infinities and tie among them by index.
+    g = (rs.standard_normal(n) * 1e-3).astype(np.float32)
+    at = rs.choice(n, max(1, n // 50), replace=False)
+    g[at] = np.where(rs.rand(at.size) < 0.5, np.float32(np.inf), np.float32(-np.inf))
+    yield "infinities", g, (rs.standard_normal(n) * 1e-3).astype(np.float32)
+    # sparse gradient (most rows untouched, as an embedding's): fewer non-zeros than k in places
+    g = np.zeros(n, dtype=np.float32)
+    at = rs.choice(n, max(1, n // 300), replace=False)
+    g[at] = rs.standard_normal(at.size).astype(np.float32)
+    yield "mostly_zero", g, z.copy()
