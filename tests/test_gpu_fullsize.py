@@ -215,3 +215,84 @@ def test_gpt2s_config_full_size():
                            wl.lr, strategy=strategy)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref), err_msg=f"merge strategy {strategy}")
+
+
+def test_largest_index_range_compress_and_merge():
+    # n = 2^31 - 1, the largest array the sparse entry points accept (int32 record indices), with
+    # one 1.6 G-element segment (more groups, gathered keys and records than any benchmark segment)
+    # between small ones, and a 7-element segment ending at the last index. Whole-output
+    # properties, which pin the selected set when no two magnitudes tie at a threshold, plus the
+    # oracle on the small segments and on slices of the merged weights.
+    n = (1 << 31) - 1
+    sizes = [1_000_003, n - 1_000_003 - 500_000_000 - 7, 500_000_000, 7]
+    off = synth.seg_offsets(sizes)
+    k = synth.seg_topk(sizes, 1, 100)
+    n_seg, K = len(sizes), int(k.astype(np.int64).sum())
+    out0 = np.concatenate([[0], np.cumsum(k.astype(np.int64))])
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(31)
+    r = torch.zeros(n, device=DEV)
+    ws = torch.empty(ld.ld_compress_topk_workspace(off, k), dtype=torch.uint8, device=DEV)
+    seg_of_rec = torch.repeat_interleave(torch.arange(n_seg, device=DEV), torch.from_numpy(k.astype(np.int64)).to(DEV))
+    off_t = torch.from_numpy(off).to(DEV)
+    idxs, vals = [], []
+    for t in range(2):
+        _progress(f"n = 2^31 - 1: compress t={t}")
+        g = torch.randn(n, device=DEV, generator=gen)
+        r_before = r.clone()
+        idx, val = ld.ld_compress_topk(g, r, off, k, workspace=ws)
+        torch.cuda.synchronize()
+        idxs.append(idx)
+        vals.append(val)
+        assert idx.numel() == K
+        i64 = idx.to(torch.int64)
+        assert bool((i64[1:] > i64[:-1]).all()), "records not strictly ascending"
+        assert bool((i64 >= off_t[seg_of_rec]).all()) and bool((i64 < off_t[seg_of_rec + 1]).all())
+        assert int(i64[-1]) <= n - 1 and int(i64[0]) >= 0
+        a = r_before + g
+        assert bool((r[i64] == 0).all()) and not bool(torch.signbit(r[i64]).any())
+        assert torch.equal(val.view(torch.int32), a[i64].view(torch.int32)), "val is not r+g bit for bit"
+        a[i64] = 0.0
+        assert torch.equal(a.view(torch.int32), r.view(torch.int32)), "unselected residual is not r+g"
+        del a
+        for s in range(n_seg):
+            lo, hi = int(off[s]), int(off[s + 1])
+            o0, o1 = int(out0[s]), int(out0[s + 1])
+            assert float(r[lo:hi].abs().max()) <= float(val[o0:o1].abs().min()), f"segment {s}: threshold violated"
+        for s in (0, 3):
+            lo, hi = int(off[s]), int(off[s + 1])
+            oi, ov, orr = oracle.topk_ef(g[lo:hi].cpu().numpy(), r_before[lo:hi].cpu().numpy(),
+                                         np.array([0, hi - lo], np.int64), k[s:s + 1], select=True)
+            o0, o1 = int(out0[s]), int(out0[s + 1])
+            np.testing.assert_array_equal(idx[o0:o1].cpu().numpy().astype(np.int64), oi.astype(np.int64) + lo)
+            np.testing.assert_array_equal(bits(val[o0:o1].cpu().numpy()), bits(ov))
+            np.testing.assert_array_equal(bits(r[lo:hi].cpu().numpy()), bits(orr))
+        del g, r_before
+    _progress("n = 2^31 - 1: merge")
+    del r, ws
+    w = torch.randn(n, device=DEV, generator=gen) * 0.02
+    slices = [(0, 2_000_000), (int(off[2]) - 1_000_000, int(off[2]) + 1_000_000), (n - 2_000_001, n)]
+    before = [w[a:b].cpu().numpy() for a, b in slices]
+    w_keep = w.clone()
+    ld.ld_merge_sparse(w, idxs, vals, 0.1)
+    torch.cuda.synchronize()
+    idx_h = [i.cpu().numpy() for i in idxs]
+    val_h = [v.cpu().numpy() for v in vals]
+    for (a, b), w0 in zip(slices, before):
+        sub_i, sub_v = [], []
+        for ih, vh in zip(idx_h, val_h):
+            p0, p1 = np.searchsorted(ih, a), np.searchsorted(ih, b)
+            sub_i.append((ih[p0:p1].astype(np.int64) - a).astype(np.int32))
+            sub_v.append(vh[p0:p1])
+        ref = oracle.merge_sparse(w0, sub_i, sub_v, 0.1)
+        np.testing.assert_array_equal(bits(w[a:b].cpu().numpy()), bits(ref), err_msg=f"merge slice [{a},{b})")
+    touched = torch.zeros(n, dtype=torch.bool, device=DEV)
+    for i in idxs:
+        touched[i.to(torch.int64)] = True
+    assert torch.equal(w[~touched].view(torch.int32), w_keep[~touched].view(torch.int32))
+    # every touched element moved by the rounded products, in order: redo them with torch on the GPU
+    ref = w_keep
+    for i, v in zip(idxs, vals):
+        i64 = i.to(torch.int64)
+        ref[i64] = ref[i64] - torch.tensor(0.1, dtype=torch.float32, device=DEV) * v
+    assert torch.equal(w.view(torch.int32), ref.view(torch.int32)), "merge differs from the per-record definition"
