@@ -9,13 +9,7 @@
 
 #define LD_WAVE 64
 
-#define LD_CHECK_HIP(expr)                         \
-    do {                                           \
-        hipError_t e_ = (expr);                    \
-        if (e_ != hipSuccess) return LD_ERR_HIP;   \
-    } while (0)
-
-// A launch that failed to enqueue leaves a sticky-free error we must consume.
+// Status of the launches enqueued since the last check (reading it also clears the error).
 static inline ld_status ld_launch_status() {
     return hipGetLastError() == hipSuccess ? LD_OK : LD_ERR_HIP;
 }
