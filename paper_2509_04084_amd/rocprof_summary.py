@@ -62,8 +62,8 @@ def pmc(db_paths) -> str:
     return "\n".join(out)
 
 
-COMPRESS_KERNELS = ("k_upload", "k_prep", "k_main", "k_hist", "k_bin", "k_gather", "k_select", "k_emit",
-                    "k_full_level<1>", "k_full_level<2>", "k_full_level<3>", "k_full_count", "k_full_emit")
+# kernel-name prefixes (template arguments follow some of them)
+COMPRESS_KERNELS = ("k_upload", "k_prep", "k_main", "k_hist", "k_bin", "k_gather", "k_select", "k_emit", "k_full_")
 
 
 def _table(path):
@@ -83,9 +83,9 @@ def traffic(sparse_txt: str, dense_txt: str, compress_calls: int = 20, snapshot_
     ff = 1024.0 / S[("k_snapshot", "FETCH_SIZE")][1]
     fw = 1024.0 / S[("k_snapshot", "WRITE_SIZE")][1]
 
-    def total(rows, names, calls):
-        f = sum(rows[(k, "FETCH_SIZE")][0] * rows[(k, "FETCH_SIZE")][1] for k in names if (k, "FETCH_SIZE") in rows)
-        w = sum(rows[(k, "WRITE_SIZE")][0] * rows[(k, "WRITE_SIZE")][1] for k in names if (k, "WRITE_SIZE") in rows)
+    def total(rows, prefixes, calls):
+        f = sum(n * v for (k, c), (n, v) in rows.items() if c == "FETCH_SIZE" and k.startswith(tuple(prefixes)))
+        w = sum(n * v for (k, c), (n, v) in rows.items() if c == "WRITE_SIZE" and k.startswith(tuple(prefixes)))
         return (f * ff + w * fw) / calls * mib
 
     snap = [k for k in ("k_snapshot", "k_snapshot_batch")]
@@ -95,7 +95,7 @@ def traffic(sparse_txt: str, dense_txt: str, compress_calls: int = 20, snapshot_
         "ld_compress_topk": total(S, COMPRESS_KERNELS, compress_calls),
         "ld_merge_sparse": total(S, ("k_chunks", "k_merge_sweep"), 1),
         "ld_snapshot_layers": (sf + sw - 2048.0) / snapshot_iters * mib,  # minus the calibration copy
-        "ld_merge_dense_adam": total(D, tuple({k for (k, _c) in D if k.startswith("k_adam")}), 1),
+        "ld_merge_dense_adam": total(D, ("k_adam",), 1),
     }
     lines = [f"# calibration (1 GiB plain copy): FETCH_SIZE x {ff:.3f}, WRITE_SIZE x {fw:.3f}"]
     for k, v in out.items():
