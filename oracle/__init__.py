@@ -70,6 +70,8 @@ def _load():
         lib.oracle_sparse_adam_replay.restype = ctypes.c_int
         lib.oracle_combine_sparse.argtypes = [p, p, p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, p, p]
         lib.oracle_combine_sparse.restype = ctypes.c_int64
+        lib.oracle_check_diff.argtypes = [p, p, ctypes.c_int64, ctypes.c_int64, p]
+        lib.oracle_check_diff.restype = None
         d = ctypes.c_double
         lib.oracle_wasted_time.argtypes = [d] * 10
         lib.oracle_wasted_time.restype = d
@@ -201,6 +203,16 @@ def combine_sparse(idx_list, val_list, n: int, scale: float = 1.0):
     if cnt < 0:
         raise ValueError("oracle_combine_sparse: index out of range or not ascending")
     return out_i[:cnt].copy(), out_v[:cnt].copy()
+
+
+def check_diff(idx, val, n: int):
+    """(out of range, not ascending, NaN) counts of one differential; `val` may be None."""
+    i = _c(idx, np.int32)
+    v = None if val is None else _c(val, np.float32)
+    out = np.zeros(3, dtype=np.int64)
+    _load().oracle_check_diff(_ptr(i), _ptr(v) if v is not None else ctypes.c_void_p(0), int(i.shape[0]), int(n),
+                              _ptr(out))
+    return tuple(int(x) for x in out)
 
 
 def wasted_time(N, T, M, tau, f, b, R_F, R_B, C_F, C_B) -> float:

@@ -29,6 +29,9 @@
 //       Sec. V-C, Eqs. (8)-(12), written term by term.
 //   oracle_combine_sparse : Sync of Algorithm 1 / Eq. (3) on the all-gathered
 //       per-worker record lists: values at equal indices added in worker order.
+//   oracle_check_diff : what the Recovery loop of Algorithm 1 takes for granted about a
+//       differential it has loaded from storage (indices in range, strictly ascending,
+//       values that are numbers), counted record by record.
 //   oracle_sparse_adam_replay : the Recovery loop of Algorithm 1 with the update
 //       the paper itself names there (decompress, then Adam on model and optimizer
 //       state), for diffs that are sparse.
@@ -244,6 +247,20 @@ int64_t oracle_combine_sparse(const int32_t* const* idx, const float* const* val
         ++out;
     }
     return out;
+}
+
+// The Recovery loop of Algorithm 1 merges differentials it has just read back from storage.
+// The merges assume of such a differential that every index lies in [0, n), that the indices
+// ascend strictly, and that no value is a NaN. Counts, record by record, how often each
+// assumption is broken: out[0] indices out of range, out[1] records whose index does not
+// exceed its predecessor's, out[2] NaN values (val may be null: then 0).
+void oracle_check_diff(const int32_t* idx, const float* val, int64_t K, int64_t n, int64_t* out) {
+    out[0] = out[1] = out[2] = 0;
+    for (int64_t j = 0; j < K; ++j) {
+        if (idx[j] < 0 || idx[j] >= n) ++out[0];
+        if (j > 0 && idx[j] <= idx[j - 1]) ++out[1];
+        if (val && std::isnan(val[j])) ++out[2];
+    }
 }
 
 // Expected wasted GPU time of a run, Eq. (10) of Sec. V-C, for a full-checkpoint interval of f

@@ -662,3 +662,34 @@ def test_wasted_time_model_stationary_point_limits_and_textbook_case():
     # every term by hand for one small case: N=2, T=100, M=50, tau=1, f=10, b=2, R_F=3, R_B=1, C_F=4, C_B=0.5
     #   failures 2: each loses 1 + 3 + 0.5*4 = 6 -> 2 GPUs * 2 * 6 = 24; 10 full ckpts * 4 * 2 = 80; 40 diffs * 0.5 * 2 = 40
     assert abs(oracle.wasted_time(2, 100, 50, 1, 10, 2, 3, 1, 4, 0.5) - 144.0) < 1e-12
+
+
+# ------------------------------------------------------- checking a loaded diff
+
+def test_check_diff_hand_cases_and_brute_force():
+    # what the Recovery loop of Algorithm 1 assumes of a differential read back from storage
+    n = 100
+    ok = np.array([0, 3, 4, 50, 99], np.int32)
+    v = np.array([1.0, -0.0, np.inf, 1e-40, -3.5], np.float32)
+    assert oracle.check_diff(ok, v, n) == (0, 0, 0)            # infinities and denormals are values
+    assert oracle.check_diff(ok, None, n) == (0, 0, 0)
+    assert oracle.check_diff(np.zeros(0, np.int32), np.zeros(0, np.float32), n) == (0, 0, 0)
+    assert oracle.check_diff(ok, v, 99) == (1, 0, 0)           # index 99 needs n >= 100
+    # hand-counted: -1 and 100 out of range; 7 after 7 and 2 after 7 break the order; two NaN
+    idx = np.array([-1, 5, 7, 7, 2, 60, 100], np.int32)
+    val = np.array([np.nan, 1, 2, 3, 4, np.nan, 5], np.float32)
+    assert oracle.check_diff(idx, val, n) == (2, 2, 2)
+    # reversed (100, 60, 2, 7, 7, 5, -1): every step but 2 -> 7 fails to ascend
+    assert oracle.check_diff(idx[::-1].copy(), val, n) == (2, 5, 2)
+    # brute force in Python on random small arrays
+    rs = np.random.RandomState(5)
+    for _ in range(50):
+        K = rs.randint(0, 40)
+        idx = rs.randint(-3, 30, K).astype(np.int32)
+        val = rs.standard_normal(K).astype(np.float32)
+        val[rs.rand(K) < 0.1] = np.nan
+        nn = int(rs.randint(1, 30))
+        want = (sum(1 for x in idx if x < 0 or x >= nn),
+                sum(1 for j in range(1, K) if idx[j] <= idx[j - 1]),
+                sum(1 for x in val if x != x))
+        assert oracle.check_diff(idx, val, nn) == want
