@@ -23,6 +23,7 @@
  *   ld_merge_sparse_adam Recovery loop of Algorithm 1 with the paper's own update:
  *                        sparse diffs decompressed and merged through Adam into
  *                        model and optimizer state.
+ * and ld_check_diff, which counts what is wrong with a diff before it is merged.
  *
  * General conventions
  *   - Pointers marked "dev" are device (HBM) addresses of the current HIP
@@ -166,6 +167,28 @@ ld_status ld_merge_sparse(float* w, int64_t n,
                           const int32_t* const* idx, const float* const* val,
                           const int64_t* K, int32_t W, float lr,
                           void* workspace, size_t workspace_bytes, ld_stream stream);
+
+/* ------------------------------------------------------------------------
+ * ld_check_diff - does a differential that was read back from storage meet
+ * what the merges take for granted?  (Recovery loop of Algorithm 1, Sec. IV-B:
+ * differentials are loaded from storage and then merged.)  Counts, over the K
+ * records of one diff,
+ *   counts[0]  indices outside [0, n)
+ *   counts[1]  records j >= 1 with idx[j] <= idx[j-1]   (not strictly ascending)
+ *   counts[2]  values that are NaN                      (0 when val is NULL)
+ * All zero: the diff may be passed to ld_merge_sparse / ld_merge_sparse_adam /
+ * ld_combine_sparse.  Anything else: those calls would skip records or, with
+ * the scatter strategy, write outside w.
+ *
+ *   idx     dev [K] int32, 4-byte aligned
+ *   val     dev [K] fp32 or NULL, 4-byte aligned
+ *   n       0 <= n <= 2^31-1
+ *   counts  dev [3] int64, 8-byte aligned; overwritten (zeroed on the stream
+ *           first, so the same buffer can be reused call after call)
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_HIP.
+ */
+ld_status ld_check_diff(const int32_t* idx, const float* val, int64_t K, int64_t n,
+                        int64_t* counts, ld_stream stream);
 
 /* Same operation with the execution strategy chosen by the caller (a tuning and
  * test hook; the result is identical for every strategy):

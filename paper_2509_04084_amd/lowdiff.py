@@ -48,6 +48,8 @@ def load() -> ctypes.CDLL:
     lib.ld_status_string.restype = ctypes.c_char_p
     lib.ld_compress_topk_workspace.argtypes = [i32, vp]
     lib.ld_compress_topk_workspace.restype = sz
+    lib.ld_check_diff.argtypes = [vp, vp, i64, i64, vp, vp]
+    lib.ld_check_diff.restype = i32
     lib.ld_compress_topk_workspace_for.argtypes = [i32, vp, vp]
     lib.ld_compress_topk_workspace_for.restype = sz
     lib.ld_compress_topk.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
@@ -233,6 +235,22 @@ def ld_merge_dense_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grads
                                     ctypes.c_float(lr), ctypes.c_float(beta1), ctypes.c_float(beta2),
                                     ctypes.c_float(eps), _stream(stream))
     _check("ld_merge_dense_adam", st)
+
+
+def ld_check_diff(idx: torch.Tensor, val: Optional[torch.Tensor], n: int,
+                  counts: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Counts (indices out of range, records not strictly ascending, NaN values) of one diff.
+    Returns the 3-element int64 device tensor `counts`; all zero means the diff can be merged."""
+    if val is not None and val.numel() != idx.numel():
+        raise ValueError("idx and val differ in length")
+    if counts is None:
+        counts = torch.empty(3, dtype=torch.int64, device=idx.device)
+    if counts.numel() < 3:
+        raise ValueError("counts needs 3 elements")
+    st = load().ld_check_diff(_dev(idx, torch.int32, "idx"), _dev(val, torch.float32, "val"),
+                              int(idx.numel()), int(n), _dev(counts, torch.int64, "counts"), _stream(stream))
+    _check("ld_check_diff", st)
+    return counts
 
 
 def ld_merge_sparse_adam_workspace(n: int, K: Sequence[int]) -> int:

@@ -85,6 +85,18 @@ def test_compress_workspace_for_density():
     assert lib.ld_compress_topk_workspace_for(2, _p(off), ctypes.c_void_p(0)) == 0
 
 
+def test_check_diff_argument_errors():
+    lib = ld.load()
+    V = ctypes.c_void_p
+    lib.ld_check_diff.restype = ctypes.c_int32
+    assert lib.ld_check_diff(V(FAKE), V(FAKE), -1, 10, V(FAKE), V(0)) == -2
+    assert lib.ld_check_diff(V(FAKE), V(FAKE), 5, 2 ** 31, V(FAKE), V(0)) == -2
+    assert lib.ld_check_diff(V(FAKE), V(FAKE), 5, 10, V(0), V(0)) == -1
+    assert lib.ld_check_diff(V(0), V(FAKE), 5, 10, V(FAKE), V(0)) == -1
+    assert lib.ld_check_diff(V(FAKE + 2), V(FAKE), 5, 10, V(FAKE), V(0)) == -5
+    assert lib.ld_check_diff(V(FAKE), V(FAKE), 5, 10, V(FAKE + 4), V(0)) == -5
+
+
 def test_merge_sparse_argument_errors():
     lib = ld.load()
     V = ctypes.c_void_p

@@ -516,6 +516,32 @@ def test_snapshot_into_pinned_host_memory():
         assert torch.equal(b.view(torch.int16), a.cpu().view(torch.int16))
 
 
+# ------------------------------------------------------ checking a loaded diff
+
+def test_check_diff_counts_match_oracle():
+    n = 5_000_000
+    rs = np.random.RandomState(3)
+    good = np.sort(rs.choice(n, 300_001, replace=False)).astype(np.int32)
+    vals = rs.standard_normal(good.size).astype(np.float32)
+    cases = {"good": (good, vals), "no values": (good, None), "empty": (good[:0], vals[:0]), "one": (good[:1], vals[:1])}
+    bad = good.copy()
+    bv = vals.copy()
+    # damage at the start, at workgroup boundaries (2048 records each), in the ragged tail
+    for j in (0, 1, 2047, 2048, 2049, 4096, 100_000, 299_999, 300_000):
+        bad[j] = bad[j - 1] if j and j % 2 else (-7 if j % 3 == 0 else n + j)
+    bv[[0, 2048, 123_456, 300_000]] = np.nan
+    bv[5] = np.inf
+    cases["damaged"] = (bad, bv)
+    cases["descending"] = (good[::-1].copy(), vals)
+    cases["all equal"] = (np.full(10_000, 17, np.int32), np.zeros(10_000, np.float32))
+    counts = torch.empty(3, dtype=torch.int64, device=DEV)
+    for name, (i, v) in cases.items():
+        got = ld.ld_check_diff(to_gpu(i), None if v is None else to_gpu(v), n, counts)
+        torch.cuda.synchronize()
+        assert tuple(got.cpu().tolist()) == oracle.check_diff(i, v, n), name
+    assert tuple(ld.ld_check_diff(to_gpu(good), to_gpu(vals), int(good[-1])).cpu().tolist()) == (1, 0, 0)
+
+
 # ------------------------------------------------------------ graph capture
 
 def test_calls_can_be_captured_in_a_graph_and_replayed():
