@@ -37,9 +37,11 @@
 //   * a tile with more candidates than its slot holds is marked, its residual is
 //     stored unzeroed, and the later passes re-read that tile from the residual;
 //   * a segment with fewer than k candidates, or with more keys in bin b than the
-//     gather list holds (massive ties), gets its residual restored from the slots
-//     and is handed to the k_full_* kernels: a plain three-level radix select over
-//     the whole segment.
+//     gather list holds, gets its residual restored from the slots and is handed to
+//     the k_full_* kernels: a plain three-level radix select over the whole segment -
+//     unless the overfull bin holds one value only (massive ties: zeros of a frozen
+//     layer, values on a grid): then that value is the threshold and its ties are
+//     taken in index order without leaving the candidate path.
 // The slot size (256 .. 2048 candidates per tile) and the lanes per tile of the candidate
 // passes (16, 32 or 64) are chosen per call from the densities seg_k / n_s, so that calls
 // at 5 or 10 % keep the same structure (the paper varies rho from 0.001 to 0.1, Exp. 10).
@@ -109,7 +111,8 @@ struct SegState {       // 64 bytes
     uint32_t mode;      // kModeCand | kModeFull
     uint32_t gcount;    // keys gathered from the threshold bin
     uint32_t fdone[4];  // tickets of the full-segment path: level 1, 2, 3, count
-    uint32_t pad[5];
+    uint32_t kmin, kmax;  // bounds of the threshold-bin keys that found no room in the gather list
+    uint32_t pad[3];
 };
 
 struct Ctx {
@@ -456,6 +459,7 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
         c.state[s].tau = tau;
         c.state[s].sh = binsh;
         c.state[s].test = test;
+        c.state[s].kmin = 0xFFFFFFFFu;
     }
     for (int32_t q = threadIdx.x; q < ngroup; q += kPrepThreads)
         c.gdesc[d.group0 + q] = GroupDesc{align_down4(off) + static_cast<int64_t>(q) * kGroup, off, end, d.out0,
@@ -820,11 +824,50 @@ __global__ __launch_bounds__(kThreads) void k_bin(Ctx c) {
     }
 }
 
+// Keys of the threshold bin held by the lanes of a wave (bit j of `in`: candidate j of the lane)
+// go to the segment's gather list: one reservation for the wave. Returns what found no room.
+// Kept out of line: the loop around it is bound by instruction fetch, and this runs for a few
+// keys per segment only.
+struct Unplaced { uint32_t kmin, kmax; bool full; };
+
+__device__ __attribute__((noinline)) Unplaced gather_lane_keys(SegState* st, uint32_t* gkey, int32_t* gtile,
+                                                               uint32_t gcap, ld_f32x4 va, ld_f32x4 vb, uint32_t in,
+                                                               int32_t tile, bool full) {
+    const float v[kPerLane] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
+    Unplaced un{0xFFFFFFFFu, 0u, full};
+    const int lane = ld_lane();
+    const uint32_t n_in = __popc(in);
+    const uint32_t inc = ld_wave_iscan(n_in);
+    const uint32_t total = static_cast<uint32_t>(__shfl(static_cast<int>(inc), LD_WAVE - 1, LD_WAVE));
+    uint32_t base = gcap;
+    if (!full) {
+        if (lane == 0) base = atomicAdd(&st->gcount, total);
+        base = static_cast<uint32_t>(__shfl(static_cast<int>(base), 0, LD_WAVE));
+        un.full = base + total > gcap;
+    }
+    uint32_t pos = base + inc - n_in;
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+        if ((in >> j) & 1u) {
+            const uint32_t key = ld_key(v[j]);
+            if (pos < gcap) {
+                gkey[pos] = key;
+                gtile[pos] = tile;
+            } else {
+                un.kmin = umin(un.kmin, key);
+                un.kmax = key > un.kmax ? key : un.kmax;
+            }
+            ++pos;
+        }
+    }
+    return un;
+}
+
 // Per tile: candidates in bins above the threshold bin; the keys inside the bin
 // are gathered per segment.
 template <int ROW>
 __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r, Ctx c) {
-    __shared__ uint32_t wsum[kWaves];
+    __shared__ uint32_t wsum[2][kWaves];
     const uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
     SegState* st = c.state + gr.seg;
@@ -836,7 +879,13 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     int32_t* gtile = c.gtile + gather_first(gr.seg, gr.lo);
     const uint32_t gcap = gather_cap(gr.lo, gr.hi);
     const int32_t tile0 = blockIdx.x * kTilesPerGroup + w * kTilesPerWave;
-    uint32_t part_gt = 0;  // fast path: the first lane of a row sums the row's tiles
+    // Keys of the threshold bin go to the segment's gather list, one reservation per wave and
+    // batch. When the list is full (massive ties: millions of equal keys) nothing more is
+    // reserved (a wave learns that from its first reservation that comes back beyond the end);
+    // the keys that found no room only widen the segment's [kmin, kmax].
+    bool full = false;
+    uint32_t lmin = 0xFFFFFFFFu, lmax = 0;
+    uint32_t part_gt = 0, part_eq = 0;  // fast path: the first lane of a row sums the row's tiles
     Trip Q, N;
     trip_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
@@ -850,32 +899,50 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
             cnt += valid && bin > b1;
             in |= static_cast<uint32_t>(valid && bin == b1) << j;
         }
-        if (__ballot(in != 0)) {  // a few keys per segment only
+        const uint32_t n_in = __popc(in);
+        const uint64_t who = __ballot(in != 0);
+        if (who) {
+            if (full || __popcll(who) >= 4) {  // massive ties: one reservation for the wave, or none
+                const Unplaced un = gather_lane_keys(st, gkey, gtile, gcap, ld_f32x4{Q.v[0], Q.v[1], Q.v[2], Q.v[3]},
+                                                     ld_f32x4{Q.v[4], Q.v[5], Q.v[6], Q.v[7]}, in, tile0 + Q.u, full);
+                lmin = umin(lmin, un.kmin);
+                lmax = un.kmax > lmax ? un.kmax : lmax;
+                full = un.full;
+            } else {  // the usual case: a key or two
 #pragma unroll
-            for (int j = 0; j < kPerLane; ++j) {
-                if ((in >> j) & 1u) {
-                    const uint32_t pos = atomicAdd(&st->gcount, 1u);
-                    if (pos < gcap) {
-                        gkey[pos] = ld_key(Q.v[j]);
-                        gtile[pos] = tile0 + Q.u;
+                for (int j = 0; j < kPerLane; ++j) {
+                    if ((in >> j) & 1u) {
+                        const uint32_t key = ld_key(Q.v[j]);
+                        const uint32_t pos = atomicAdd(&st->gcount, 1u);
+                        if (pos < gcap) {
+                            gkey[pos] = key;
+                            gtile[pos] = tile0 + Q.u;
+                        } else {
+                            lmin = umin(lmin, key);
+                            lmax = key > lmax ? key : lmax;
+                        }
                     }
                 }
             }
         }
-        cnt = row_sum<ROW>(cnt);
+        const uint32_t both = row_sum<ROW>(cnt | (n_in << 16));  // a tile holds at most 512 here
+        cnt = both & 0xFFFFu;
+        const uint32_t eqc = both >> 16;
         if ((lane & (ROW - 1)) == 0 && Q.cn <= Rows<ROW>::kFast) {
             c.tile_gt[tile0 + Q.u] = cnt;
-            c.tile_eq[tile0 + Q.u] = 0;
+            c.tile_eq[tile0 + Q.u] = eqc;  // keys in the threshold bin; k_select takes out those that are not T
             part_gt += cnt;
+            part_eq += eqc;
         }
         Q = N;
     }
-    uint32_t slow_gt = 0, gt = 0;
+    uint32_t slow_gt = 0, slow_eq = 0, gt = 0, eq = 0;
     int32_t tile_of_item = 0;
     slow_tiles<false, ROW>(
         c, r, gr, blockIdx.x, mycnt, tau,
         [&](int u) {
             gt = 0;
+            eq = 0;
             tile_of_item = tile0 + u;
         },
         [&](bool have, float v, uint32_t, bool) {
@@ -885,29 +952,56 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
             const bool in = have && bin == b1;
             const uint64_t min_ = __ballot(in);
             if (min_) {
-                uint32_t base = 0;
-                if (lane == 0) base = atomicAdd(&st->gcount, static_cast<uint32_t>(__popcll(min_)));
-                base = __shfl(base, 0, LD_WAVE);
+                const uint32_t total = static_cast<uint32_t>(__popcll(min_));
+                eq += total;
+                uint32_t base = gcap;
+                if (!full) {
+                    if (lane == 0) base = atomicAdd(&st->gcount, total);
+                    base = static_cast<uint32_t>(__shfl(static_cast<int>(base), 0, LD_WAVE));
+                    full = base + total > gcap;
+                }
                 const uint32_t pos = base + mbcnt(min_);
-                if (in && pos < gcap) {
-                    gkey[pos] = key;
-                    gtile[pos] = tile_of_item;
+                if (in) {
+                    if (pos < gcap) {
+                        gkey[pos] = key;
+                        gtile[pos] = tile_of_item;
+                    } else {
+                        lmin = umin(lmin, key);
+                        lmax = key > lmax ? key : lmax;
+                    }
                 }
             }
         },
         [&](int u) {
             if (lane == 0) {
                 c.tile_gt[tile0 + u] = gt;
-                c.tile_eq[tile0 + u] = 0;
+                c.tile_eq[tile0 + u] = eq;
             }
             slow_gt += gt;
+            slow_eq += eq;
         });
+    if (__ballot(lmin <= lmax)) {  // some key of this wave found no room
+#pragma unroll
+        for (int d = LD_WAVE / 2; d > 0; d >>= 1) {
+            lmin = umin(lmin, static_cast<uint32_t>(__shfl_xor(static_cast<int>(lmin), d, LD_WAVE)));
+            const uint32_t o = static_cast<uint32_t>(__shfl_xor(static_cast<int>(lmax), d, LD_WAVE));
+            lmax = o > lmax ? o : lmax;
+        }
+        if (lane == 0) {
+            atomicMin(&st->kmin, lmin);
+            atomicMax(&st->kmax, lmax);
+        }
+    }
     const uint32_t wave_gt = ld_wave_sum(part_gt) + slow_gt;
-    if (lane == 0) wsum[w] = wave_gt;
+    const uint32_t wave_eq = ld_wave_sum(part_eq) + slow_eq;
+    if (lane == 0) {
+        wsum[0][w] = wave_gt;
+        wsum[1][w] = wave_eq;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
-        c.group_gt[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-        c.group_eq[blockIdx.x] = 0;
+        c.group_gt[blockIdx.x] = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
+        c.group_eq[blockIdx.x] = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
     }
 }
 
@@ -927,48 +1021,73 @@ __global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
     const uint32_t ng = st->gcount;
     const uint32_t* gkey = c.gkey + gather_first(gr.seg, gr.lo);
     const int32_t* gtile = c.gtile + gather_first(gr.seg, gr.lo);
-    if (ng > gather_cap(gr.lo, gr.hi)) {
-        mark_full(c, st, gr, &list0);  // too many keys share the threshold bin (massive ties)
-        return;
-    }
-    const uint32_t b1 = st->prefix, binsh = st->sh;
-    const uint32_t base = st->tau + (b1 << binsh);
-    const int bits = (b1 == static_cast<uint32_t>(kTopBin)) ? 31 : static_cast<int>(binsh);  // the top bin is open-ended
-    const int nlev = bits == 0 ? 1 : (bits + 10) / 11;
-    uint32_t prefix = 0, krem = st->krem;
-#pragma unroll 1
-    for (int lev = 0; lev < nlev; ++lev) {
-        const int shift = 11 * (nlev - 1 - lev);
-        for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+    const uint32_t gcap = gather_cap(gr.lo, gr.hi);
+    uint32_t T, m;
+    uint32_t seen = 0;
+    if (ng > gcap) {
+        // More keys in the threshold bin than the list holds. If they are all one value (massive
+        // ties: a frozen layer's zeros, values on a coarse grid) nothing has to be selected among
+        // them: T is that value, and the rank left inside the bin is the number of ties to keep,
+        // lowest index first. k_gather's per-tile counts of the bin are then the tie counts.
+        if (threadIdx.x == 0) { res[0] = st->kmin; res[1] = st->kmax; }
         __syncthreads();
+        uint32_t lmin = 0xFFFFFFFFu, lmax = 0;
+#pragma unroll 1
+        for (uint32_t p = threadIdx.x; p < gcap; p += kThreads) {
+            const uint32_t key = gkey[p];
+            lmin = umin(lmin, key);
+            lmax = key > lmax ? key : lmax;
+        }
+        atomicMin(&res[0], lmin);
+        atomicMax(&res[1], lmax);
+        __syncthreads();
+        if (res[0] != res[1]) {
+            mark_full(c, st, gr, &list0);  // several values share an overfull bin
+            return;
+        }
+        T = res[0];
+        m = st->krem;
+        __syncthreads();
+    } else {
+        const uint32_t b1 = st->prefix, binsh = st->sh;
+        const uint32_t base = st->tau + (b1 << binsh);
+        const int bits = (b1 == static_cast<uint32_t>(kTopBin)) ? 31 : static_cast<int>(binsh);  // the top bin is open-ended
+        const int nlev = bits == 0 ? 1 : (bits + 10) / 11;
+        uint32_t prefix = 0, krem = st->krem;
+#pragma unroll 1
+        for (int lev = 0; lev < nlev; ++lev) {
+            const int shift = 11 * (nlev - 1 - lev);
+            for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+            __syncthreads();
+#pragma unroll 1
+            for (uint32_t p = threadIdx.x; p < ng; p += kThreads) {
+                const uint32_t rel = gkey[p] - base;
+                if (lev == 0 || ((rel ^ prefix) >> (shift + 11)) == 0) atomicAdd(&lh[(rel >> shift) & 0x7FFu], 1u);
+            }
+            __syncthreads();
+            find_bin<kThreads, false>(lh, krem, sh, res);
+            prefix |= res[0] << shift;
+            krem = res[1];
+            __syncthreads();
+        }
+        T = base + prefix;
+        m = krem;
+        // k_gather counted every key of the bin as a tie: move those above T to the counts of the
+        // selected, drop those below. The group sums are read back below by this same workgroup.
+        // The updates return their old value, so each has been performed when its result arrives;
+        // with the barrier that orders them before the reads. (A device-scope fence would do too,
+        // but it writes back the whole L2 and costs 30 us here.)
 #pragma unroll 1
         for (uint32_t p = threadIdx.x; p < ng; p += kThreads) {
-            const uint32_t rel = gkey[p] - base;
-            if (lev == 0 || ((rel ^ prefix) >> (shift + 11)) == 0) atomicAdd(&lh[(rel >> shift) & 0x7FFu], 1u);
-        }
-        __syncthreads();
-        find_bin<kThreads, false>(lh, krem, sh, res);
-        prefix |= res[0] << shift;
-        krem = res[1];
-        __syncthreads();
-    }
-    const uint32_t T = base + prefix, m = krem;
-    // The group sums are read back below by this same workgroup. The updates return their old
-    // value, so each has been performed when its result arrives; with the barrier that orders
-    // them before the reads. (A device-scope fence would do too, but it writes back the whole
-    // L2 and costs 30 us here.)
-    uint32_t seen = 0;
-#pragma unroll 1
-    for (uint32_t p = threadIdx.x; p < ng; p += kThreads) {
-        const uint32_t key = gkey[p];
-        if (key < T) continue;
-        const int32_t tile = gtile[p];
-        if (key > T) {
-            atomicAdd(c.tile_gt + tile, 1u);
-            seen |= atomicAdd(c.group_gt + tile / kTilesPerGroup, 1u);
-        } else {
-            atomicAdd(c.tile_eq + tile, 1u);
-            seen |= atomicAdd(c.group_eq + tile / kTilesPerGroup, 1u);
+            const uint32_t key = gkey[p];
+            if (key == T) continue;
+            const int32_t tile = gtile[p];
+            atomicSub(c.tile_eq + tile, 1u);
+            seen |= atomicSub(c.group_eq + tile / kTilesPerGroup, 1u);
+            if (key > T) {
+                atomicAdd(c.tile_gt + tile, 1u);
+                seen |= atomicAdd(c.group_gt + tile / kTilesPerGroup, 1u);
+            }
         }
     }
     if (seen == 0xFFFFFFFFu) res[0] = seen;  // never true: keeps the results, and so the waits, alive

@@ -99,6 +99,38 @@ def test_compress_density_range(rho):
     np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(orr))
 
 
+def test_compress_massive_ties_at_the_threshold():
+    # More equal keys at the threshold than a segment's gather list holds (4096 + n_s / 4096).
+    # One repeated value (zeros of a frozen layer, values on a grid): taken by index order without
+    # leaving the candidate path. Two adjacent values sharing one overfull bin: the full-segment
+    # path. Both must give the oracle's records, bit for bit.
+    rs = np.random.RandomState(17)
+    n = 1_000_000
+    off = np.array([0, n], np.int64)
+    k = np.array([10_000], np.int32)
+    base = (rs.standard_normal(n) * 1e-3).astype(np.float32)
+    order = np.argsort(-np.abs(base), kind="stable")
+    cluster = order[7_000:13_000]                 # ranks around k
+    lo_val = np.float32(np.abs(base[order[13_000]]))
+    one = base.copy()
+    one[cluster] = np.where(rs.rand(cluster.size) < 0.5, lo_val, -lo_val)
+    check_compress(one, np.zeros(n, np.float32), off, k, tag="one repeated value across the threshold")
+    two = one.copy()
+    up = np.nextafter(lo_val, np.float32(1.0))
+    two[cluster[::2]] = up
+    check_compress(two, np.zeros(n, np.float32), off, k, tag="two adjacent values across the threshold")
+    # frozen layer next to a live one, and values on a coarse grid (heavy duplication everywhere)
+    sizes = [600_000, 400_000]
+    off2 = synth.seg_offsets(sizes)
+    g = base.copy()
+    g[:600_000] = 0.0
+    g[123] = -0.0
+    check_compress(g, np.zeros(n, np.float32), off2, synth.seg_topk(sizes, 1, 100), tag="frozen segment")
+    grid = (np.round(base * 3e4) / 3e4).astype(np.float32)
+    check_compress(grid, (np.round(base[::-1] * 1e4) / 3e4).astype(np.float32), off2,
+                   synth.seg_topk(sizes, 1, 100), tag="values on a grid")
+
+
 def test_compress_resnet50_shape():
     wl = synth.workload("resnet50")
     g = synth.gradient(wl, 0).numpy()
