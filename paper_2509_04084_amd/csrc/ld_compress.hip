@@ -689,22 +689,35 @@ __device__ __forceinline__ void slow_tiles(const Ctx& c, const float* __restrict
         const int64_t slot = static_cast<int64_t>(tile0 + u) * c.slot;
         const int64_t tbase = tbase0 + static_cast<int64_t>(u) * kTile;
         begin(u);
+        // kAhead batches of 64 are requested before the first is handed on: a tile read back from
+        // the residual is 64 batches long, and one load at a time would wait for memory 64 times
+        constexpr int kAhead = 4;
 #pragma unroll 1
-        for (uint32_t b0 = 0; b0 < total; b0 += LD_WAVE) {
-            bool have = b0 + lane < total;
-            float v;
-            uint32_t x;
-            if (stored) {
-                v = have ? c.cval[slot + b0 + lane] : 0.0f;
-                x = (IDX && have) ? c.cidx[slot + b0 + lane] : 0u;
-            } else {
-                const int64_t e = tbase + b0 + lane;
-                const bool in = e >= gr.lo && e < gr.hi;
-                v = in ? r[e] : 0.0f;
-                x = b0 + lane;
-                have = in && ld_key(v) >= tau;
+        for (uint32_t b0 = 0; b0 < total; b0 += kAhead * LD_WAVE) {
+            bool have[kAhead];
+            float v[kAhead];
+            uint32_t x[kAhead];
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                const uint32_t at = b0 + a * LD_WAVE + lane;
+                have[a] = at < total;
+                if (stored) {
+                    v[a] = have[a] ? c.cval[slot + at] : 0.0f;
+                    x[a] = (IDX && have[a]) ? c.cidx[slot + at] : 0u;
+                } else {
+                    const int64_t e = tbase + at;
+                    have[a] = have[a] && e >= gr.lo && e < gr.hi;
+                    v[a] = have[a] ? r[e] : 0.0f;
+                    x[a] = at;
+                }
             }
-            item(have, v, x, stored);
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                if (b0 + a * LD_WAVE < total) {
+                    const bool h = stored ? have[a] : (have[a] && ld_key(v[a]) >= tau);
+                    item(h, v[a], x[a], stored);
+                }
+            }
         }
         end(u);
     }
@@ -782,8 +795,17 @@ __global__ __launch_bounds__(kHistGroups * kThreads) void k_hist(const float* __
         slow_tiles<false, ROW>(
             c, r, gr, group, mycnt, tau, [](int) {},
             [&](bool have, float v, uint32_t, bool) {
-                if (have) {
-                    const uint32_t bin = fine_bin(ld_key(v), tau, binsh);
+                const uint32_t bin = fine_bin(ld_key(v), tau, binsh);
+                const uint64_t any = __ballot(have);
+                if (any == 0) return;
+                // massive ties put a whole batch into one bin: one update instead of 64 on one counter
+                const uint32_t lead = static_cast<uint32_t>(__shfl(static_cast<int>(bin), __builtin_ctzll(any), LD_WAVE));
+                if (__ballot(have && bin == lead) == any) {
+                    if (ld_lane() == 0) {
+                        if (lead == static_cast<uint32_t>(kTopBin)) top += __popcll(any);
+                        else atomicAdd(&lh[q][lead], static_cast<uint32_t>(__popcll(any)));
+                    }
+                } else if (have) {
                     if (bin == static_cast<uint32_t>(kTopBin)) ++top; else atomicAdd(&lh[q][bin], 1u);
                 }
             },
