@@ -320,7 +320,7 @@ extern "C" ld_status ld_combine_sparse(const int32_t* const* idx, const float* c
     uint32_t* gsum = reinterpret_cast<uint32_t*>(ws + L.gsum);
     uint32_t* goff = reinterpret_cast<uint32_t*>(ws + L.goff);
     static_assert(LD_MAX_WORKERS <= kGroupMax, "one launch must hold every list");
-    DiffTable tb;
+    DiffTable tb = {};
     for (int32_t t = 0; t < kGroupMax; ++t) {
         const bool live = t < N;
         tb.idx[t] = live ? idx[t] : nullptr;

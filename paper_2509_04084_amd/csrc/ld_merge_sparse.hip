@@ -28,9 +28,11 @@ namespace {
 constexpr int kSub = 8192;                 // elements per wave sub-tile (32 KB of LDS, 5 waves per CU)
 constexpr int kChunkSubs = 6;              // sub-tiles per chunk of the range table
 static_assert(static_cast<int64_t>(kSub) * kChunkSubs == kChunk, "sub-tiles must tile a chunk");
-constexpr int kWin = 2;                    // 64-record windows per diff loaded ahead
-constexpr int kPre = 10;                   // diffs whose windows are loaded before any is applied
 constexpr int kMargin = 24;                // records the window starts before the interpolated position
+constexpr int kSweepGroup = kTableMax;     // diffs per sweep: a lane keeps the chunk ranges of two of them
+// Windows loaded ahead, as <diffs per batch, 64-record windows per diff>: 10 x 2 for the usual
+// densities (~80 records per diff and sub-tile at 1 %), 20 x 1 for long windows of very sparse
+// diffs (a handful of records each: half as many rounds of loads, each a memory round trip).
 
 __device__ __forceinline__ void apply_record(float* tile, int32_t local, float val, float lr) {
     const float p = __fmul_rn(lr, val);        // rounded product: never fused
@@ -63,25 +65,36 @@ __device__ __forceinline__ void apply_from(float* tile, const int32_t* __restric
     }
 }
 
-// The first kWin * 64 records of kPre consecutive diffs at and after the guessed positions.
-struct Batch {
-    int32_t s[kPre], e[kPre], b[kPre];   // window start, end of the chunk's records, their begin (wave-uniform)
-    int32_t ri[kPre][kWin];
-    float rv[kPre][kWin];
+// Chunk range [c0, c1) and guessed start of diff t (lanes 0..63) and of diff t + 64 (second set).
+struct Ranges {
+    int32_t c0[2], c1[2], start[2];
 };
 
-__device__ __forceinline__ void load_batch(Batch& X, const DiffTable& tb, int32_t W, int32_t t0, int32_t start,
-                                           int32_t c0, int32_t c1, int lane) {
+__device__ __forceinline__ int32_t of_diff(const int32_t (&x)[2], int t) {
+    return t < LD_WAVE ? __builtin_amdgcn_readlane(x[0], t) : __builtin_amdgcn_readlane(x[1], t - LD_WAVE);
+}
+
+// The first WIN * 64 records of PRE consecutive diffs at and after the guessed positions.
+template <int PRE, int WIN>
+struct Batch {
+    int32_t s[PRE], e[PRE], b[PRE];   // window start, end of the chunk's records, their begin (wave-uniform)
+    int32_t ri[PRE][WIN];
+    float rv[PRE][WIN];
+};
+
+template <int PRE, int WIN>
+__device__ __forceinline__ void load_batch(Batch<PRE, WIN>& X, const DiffTable& tb, int32_t W, int32_t t0,
+                                           const Ranges& R, int lane) {
 #pragma unroll
-    for (int g = 0; g < kPre; ++g) {
+    for (int g = 0; g < PRE; ++g) {
         const int t = (t0 + g < W) ? t0 + g : 0;
-        X.s[g] = __builtin_amdgcn_readlane(start, t);
-        X.b[g] = __builtin_amdgcn_readlane(c0, t);
-        X.e[g] = (t0 + g < W) ? __builtin_amdgcn_readlane(c1, t) : X.s[g];  // past W: an empty window
+        X.s[g] = of_diff(R.start, t);
+        X.b[g] = of_diff(R.c0, t);
+        X.e[g] = (t0 + g < W) ? of_diff(R.c1, t) : X.s[g];  // past W: an empty window
         const int32_t* __restrict__ ip = tb.idx[t];
         const float* __restrict__ vp = tb.val[t];
 #pragma unroll
-        for (int u = 0; u < kWin; ++u) {
+        for (int u = 0; u < WIN; ++u) {
             const int32_t p = X.s[g] + u * LD_WAVE + lane;
             const bool h = p < X.e[g];
             X.ri[g][u] = h ? ip[p] : INT_MAX;
@@ -90,6 +103,7 @@ __device__ __forceinline__ void load_batch(Batch& X, const DiffTable& tb, int32_
     }
 }
 
+template <int PRE, int WIN>
 __global__ __launch_bounds__(LD_WAVE) void k_merge_sweep(float* __restrict__ w, int64_t n, int32_t nchunk,
                                                          DiffTable tb, int32_t W,
                                                          const int32_t* __restrict__ ctab, float lr) {
@@ -112,21 +126,26 @@ __global__ __launch_bounds__(LD_WAVE) void k_merge_sweep(float* __restrict__ w, 
         for (int j = 0; j < kSub / 4 / LD_WAVE; ++j) x[j] = ld_nt_load(src + j * LD_WAVE + lane);
     }
 
-    // lane t: where diff t's records of this chunk lie, and the guess for this sub-tile
+    // lane t: where the records of diffs t and t + 64 lie in this chunk, and the guesses for this sub-tile
     const int32_t chunk = static_cast<int32_t>(sub / kChunkSubs), part = static_cast<int32_t>(sub % kChunkSubs);
-    int32_t c0 = 0, c1 = 0;
-    if (lane < W) {
-        const int32_t* row = ctab + static_cast<int64_t>(lane) * (nchunk + 1) + chunk;
-        c0 = row[0];
-        c1 = row[1];
+    Ranges R;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int t = h * LD_WAVE + lane;
+        R.c0[h] = R.c1[h] = 0;
+        if (t < W) {
+            const int32_t* row = ctab + static_cast<int64_t>(t) * (nchunk + 1) + chunk;
+            R.c0[h] = row[0];
+            R.c1[h] = row[1];
+        }
+        R.start[h] = R.c0[h] + ((R.c1[h] - R.c0[h]) * part) / kChunkSubs - kMargin;
+        if (R.start[h] < R.c0[h]) R.start[h] = R.c0[h];
     }
-    int32_t start = c0 + ((c1 - c0) * part) / kChunkSubs - kMargin;
-    if (start < c0) start = c0;
 
-    // The windows of the first kPre diffs are requested before the tile goes to LDS. (Requesting
+    // The windows of the first PRE diffs are requested before the tile goes to LDS. (Requesting
     // every next batch while the current one is applied made the sweep 10 % slower.)
-    Batch A;
-    load_batch(A, tb, W, 0, start, c0, c1, lane);
+    Batch<PRE, WIN> A;
+    load_batch(A, tb, W, 0, R, lane);
 
     if (full) {
 #pragma unroll
@@ -136,10 +155,10 @@ __global__ __launch_bounds__(LD_WAVE) void k_merge_sweep(float* __restrict__ w, 
     }
     __syncthreads();  // one wave: only orders the vector fill before the scalar updates
 
-    for (int32_t t0 = 0; t0 < W; t0 += kPre) {
-        if (t0 > 0) load_batch(A, tb, W, t0, start, c0, c1, lane);
+    for (int32_t t0 = 0; t0 < W; t0 += PRE) {
+        if (t0 > 0) load_batch(A, tb, W, t0, R, lane);
 #pragma unroll
-        for (int g = 0; g < kPre; ++g) {
+        for (int g = 0; g < PRE; ++g) {
             if (A.s[g] < A.e[g]) {
                 const int t = t0 + g;
                 const int32_t first = __builtin_amdgcn_readfirstlane(A.ri[g][0]);
@@ -147,13 +166,13 @@ __global__ __launch_bounds__(LD_WAVE) void k_merge_sweep(float* __restrict__ w, 
                     // the window begins before the sub-tile's records do
                     bool more = true;
 #pragma unroll
-                    for (int u = 0; u < kWin; ++u) {
+                    for (int u = 0; u < WIN; ++u) {
                         if (more) {
                             if (A.ri[g][u] >= lo && A.ri[g][u] < hi) apply_record(tile, A.ri[g][u] - lo, A.rv[g][u], lr);
                             more = !__ballot(A.ri[g][u] >= hi);
                         }
                     }
-                    if (more) apply_from(tile, tb.idx[t], tb.val[t], A.s[g] + kWin * LD_WAVE, A.e[g], lo, hi, lr, lane);
+                    if (more) apply_from(tile, tb.idx[t], tb.val[t], A.s[g] + WIN * LD_WAVE, A.e[g], lo, hi, lr, lane);
                 } else {
                     // guess too late: find the first record of the sub-tile inside the chunk
                     const int32_t p = lower_bound_idx(tb.idx[t], A.b[g], A.s[g], lo);
@@ -193,7 +212,7 @@ int32_t sub_tiles(int64_t n) { return static_cast<int32_t>((n + kSub - 1) / kSub
 extern "C" size_t ld_merge_sparse_workspace(int64_t n, int32_t W, const int64_t* K) {
     (void)K;
     if (n <= 0 || W <= 0) return 256;
-    const int64_t group = W < kGroupMax ? W : kGroupMax;
+    const int64_t group = W < kSweepGroup ? W : kSweepGroup;
     return ld_round_up(static_cast<size_t>(group) * (static_cast<size_t>(chunks(n)) + 1) * 4, 256);
 }
 
@@ -230,18 +249,25 @@ extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t
         return LD_ERR_WORKSPACE;
     const int32_t nsub = sub_tiles(n), nchunk = chunks(n);
     int32_t* ctab = static_cast<int32_t*>(workspace);
-    for (int32_t g0 = 0; g0 < W; g0 += kGroupMax) {
-        const int32_t gw = (W - g0) < kGroupMax ? (W - g0) : kGroupMax;
-        DiffTable tb;
-        for (int32_t t = 0; t < kGroupMax; ++t) {
+    for (int32_t g0 = 0; g0 < W; g0 += kSweepGroup) {
+        const int32_t gw = (W - g0) < kSweepGroup ? (W - g0) : kSweepGroup;
+        DiffTable tb = {};
+        int64_t most = 0;
+        for (int32_t t = 0; t < kTableMax; ++t) {
             const bool live = t < gw;
             tb.idx[t] = live ? idx[g0 + t] : nullptr;
             tb.val[t] = live ? val[g0 + t] : nullptr;
             tb.K[t] = live ? static_cast<int32_t>(K[g0 + t]) : 0;
+            if (live && K[g0 + t] > most) most = K[g0 + t];
         }
         launch_chunks(tb, gw, n, nchunk, ctab, s);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
-        k_merge_sweep<<<dim3((nsub + 7) / 8 * 8), dim3(LD_WAVE), 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
+        const dim3 grid((nsub + 7) / 8 * 8), wave(LD_WAVE);
+        // at most ~16 records per diff and sub-tile: one window per diff is plenty
+        if (gw > 10 && most * kSub <= 16 * n)
+            k_merge_sweep<20, 1><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
+        else
+            k_merge_sweep<10, 2><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     }
     return LD_OK;

@@ -213,7 +213,7 @@ extern "C" ld_status ld_merge_sparse_adam(float* w, float* m, float* v, int64_t 
     static_assert(kGroupMax <= LD_MAX_ADAM_STEPS, "step table too small");
     for (int32_t g0 = 0; g0 < W; g0 += kGroupMax) {
         const int32_t gw = (W - g0) < kGroupMax ? (W - g0) : kGroupMax;
-        DiffTable tb;
+        DiffTable tb = {};
         for (int32_t t = 0; t < kGroupMax; ++t) {
             const bool live = t < gw;
             tb.idx[t] = live ? idx[g0 + t] : nullptr;

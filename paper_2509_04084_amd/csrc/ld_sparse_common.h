@@ -10,12 +10,13 @@
 namespace {
 
 constexpr int64_t kChunk = 49152;          // elements per chunk of the range table
-constexpr int kGroupMax = 64;              // diffs per launch (pointer table travels as a kernel argument)
+constexpr int kGroupMax = 64;              // diffs per launch of the Adam replay and of the combine
+constexpr int kTableMax = 128;             // diffs a table holds (it travels as a kernel argument: 2.5 KB)
 
 struct DiffTable {
-    const int32_t* idx[kGroupMax];
-    const float* val[kGroupMax];
-    int32_t K[kGroupMax];
+    const int32_t* idx[kTableMax];
+    const float* val[kTableMax];
+    int32_t K[kTableMax];
 };
 
 __device__ __forceinline__ int32_t lower_bound_idx(const int32_t* __restrict__ idx, int32_t lo, int32_t hi,
