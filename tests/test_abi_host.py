@@ -201,3 +201,15 @@ def test_config_model_matches_oracle():
     assert np.isnan(ld.ld_config_wasted_time(p, 2.0, 3.0, 1.0, 1.0))         # b > f
     assert np.isnan(ld.ld_config_critical_interval(p, 2.0, 1.0, 50.0))       # C_B >= C_F
     assert ld.load().ld_config_select(None, 1, None, None, None, None, None) == -1
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    # no built library and no working compiler: the binding must raise, there is nothing to fall back to
+    from paper_2509_04084_amd import _build
+    monkeypatch.setattr(ld, "_lib", None)
+    monkeypatch.setattr(_build, "LIB", str(tmp_path / "liblowdiff.so"))
+    monkeypatch.setenv("HIPCC", "/bin/false")
+    with pytest.raises(RuntimeError):
+        ld.load()
+    with pytest.raises(RuntimeError):
+        ld.ld_compress_topk_workspace(np.array([0, 10], np.int64))
