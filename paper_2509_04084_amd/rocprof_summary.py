@@ -26,7 +26,7 @@ OURS = ("k_main", "k_prep", "k_upload", "k_hist", "k_bin", "k_gather", "k_select
 
 def _short(name: str) -> str:
     name = name.replace("(anonymous namespace)::", "").replace("void ", "")
-    return name.split("(")[0]
+    return name.split("(")[0].replace(", ", ",")  # no blanks: the summaries are parsed by column
 
 
 def _ours(name: str) -> bool:
