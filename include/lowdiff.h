@@ -3,7 +3,7 @@
  *
  * The library turns each training iteration's gradient into a differential
  * checkpoint and merges a window of such differentials onto a dense base
- * checkpoint.  Six operations, all executed by hand-written HIP kernels:
+ * checkpoint.  The operations, all executed by hand-written HIP kernels:
  *
  *   ld_compress_topk     Comp of Algorithm 1 (Sec. IV-B): the compressed
  *                        gradient that LowDiff reuses as the differential
