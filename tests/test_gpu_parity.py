@@ -548,6 +548,63 @@ def test_snapshot_into_pinned_host_memory():
         assert torch.equal(b.view(torch.int16), a.cpu().view(torch.int16))
 
 
+# ------------------------------------------------- workspaces hold anything on entry
+
+@pytest.mark.parametrize("fill", [0x00, 0xFF, 0x5A, "random"])
+def test_workspace_and_output_contents_on_entry_are_irrelevant(fill):
+    def dirty(nbytes):
+        if fill == "random":
+            return torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=DEV)
+        return torch.full((nbytes,), fill, dtype=torch.uint8, device=DEV)
+
+    sizes = [70001, 64, 300000, 0, 4097, 200000]
+    off = synth.seg_offsets(sizes)
+    k = synth.seg_topk(sizes, 1, 100) * (np.array(sizes) > 0)
+    n, K = int(off[-1]), int(k.sum())
+    rs = np.random.RandomState(9)
+    g = rs.standard_normal(n).astype(np.float32)
+    g[70065:370065][rs.rand(300000) < 0.7] = np.float32(0.25)     # massive ties in the large segment
+    r0 = (rs.standard_normal(n) * 0.1).astype(np.float32)
+    r0[70065:370065] = 0
+    oi, ov, orr = oracle.topk_ef(g, r0, off, k, select=True)
+    for strategy in (ld.LD_COMPRESS_AUTO, ld.LD_COMPRESS_FULL):
+        ws = dirty(ld.ld_compress_topk_workspace(off, k))
+        out_i = dirty(4 * K).view(torch.int32)
+        out_v = dirty(4 * K).view(torch.float32)
+        r = to_gpu(r0)
+        ld.ld_compress_topk(to_gpu(g), r, off, k, out_i, out_v, ws, strategy=strategy)
+        ld.ld_compress_topk(to_gpu(g), to_gpu(r0), off, k, out_i, out_v, ws, strategy=strategy)  # reused as left
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out_i.cpu().numpy(), oi)
+        np.testing.assert_array_equal(bits(out_v.cpu().numpy()), bits(ov))
+        np.testing.assert_array_equal(bits(r.cpu().numpy()), bits(orr))
+    # the replays and the combine on two diffs
+    g2 = rs.standard_normal(n).astype(np.float32)
+    oi2, ov2, _ = oracle.topk_ef(g2, orr, off, k, select=True)
+    idxs, vals = [oi, oi2], [ov, ov2]
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    w = to_gpu(w0)
+    ld.ld_merge_sparse(w, [to_gpu(i) for i in idxs], [to_gpu(v) for v in vals], 0.1,
+                       dirty(ld.ld_merge_sparse_workspace(n, [K, K])), strategy=ld.LD_MERGE_SWEEP)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(oracle.merge_sparse(w0, idxs, vals, 0.1)))
+    z = np.zeros(n, np.float32)
+    wa, ma, va = to_gpu(w0), to_gpu(z), to_gpu(z)
+    ld.ld_merge_sparse_adam(wa, ma, va, [to_gpu(i) for i in idxs], [to_gpu(v) for v in vals], 0, 1e-4, **synth.ADAM,
+                            workspace=dirty(ld.ld_merge_sparse_adam_workspace(n, [K, K])))
+    torch.cuda.synchronize()
+    check_adam_close((wa, ma, va), oracle.sparse_adam_replay(w0, z, z, idxs, vals, 0, 1e-4, **synth.ADAM), "sparse adam")
+    c_i, c_v, c_n = ld.ld_combine_sparse([to_gpu(i) for i in idxs], [to_gpu(v) for v in vals], n, 1.0,
+                                         dirty(8 * K).view(torch.int32), dirty(8 * K).view(torch.float32),
+                                         dirty(8).view(torch.int64), dirty(ld.ld_combine_sparse_workspace(n, 2)))
+    torch.cuda.synchronize()
+    e_i, e_v = oracle.combine_sparse(idxs, vals, n, 1.0)
+    cnt = int(c_n.item())
+    assert cnt == e_i.size
+    np.testing.assert_array_equal(c_i[:cnt].cpu().numpy(), e_i)
+    np.testing.assert_array_equal(bits(c_v[:cnt].cpu().numpy()), bits(e_v))
+
+
 # ------------------------------------------------------ checking a loaded diff
 
 def test_check_diff_counts_match_oracle():
