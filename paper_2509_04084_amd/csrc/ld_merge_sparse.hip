@@ -65,13 +65,17 @@ __device__ __forceinline__ void apply_from(float* tile, const int32_t* __restric
     }
 }
 
-// Chunk range [c0, c1) and guessed start of diff t (lanes 0..63) and of diff t + 64 (second set).
+// Chunk range [c0, c1) and guessed start of diff t (lanes 0..63) and, in sweeps of more than 64
+// diffs (SETS = 2), of diff t + 64.
+template <int SETS>
 struct Ranges {
-    int32_t c0[2], c1[2], start[2];
+    int32_t c0[SETS], c1[SETS], start[SETS];
 };
 
-__device__ __forceinline__ int32_t of_diff(const int32_t (&x)[2], int t) {
-    return t < LD_WAVE ? __builtin_amdgcn_readlane(x[0], t) : __builtin_amdgcn_readlane(x[1], t - LD_WAVE);
+template <int SETS>
+__device__ __forceinline__ int32_t of_diff(const int32_t (&x)[SETS], int t) {
+    if (SETS == 1) return __builtin_amdgcn_readlane(x[0], t);
+    return t < LD_WAVE ? __builtin_amdgcn_readlane(x[0], t) : __builtin_amdgcn_readlane(x[SETS - 1], t - LD_WAVE);
 }
 
 // The first WIN * 64 records of PRE consecutive diffs at and after the guessed positions.
@@ -82,9 +86,9 @@ struct Batch {
     float rv[PRE][WIN];
 };
 
-template <int PRE, int WIN>
+template <int PRE, int WIN, int SETS>
 __device__ __forceinline__ void load_batch(Batch<PRE, WIN>& X, const DiffTable& tb, int32_t W, int32_t t0,
-                                           const Ranges& R, int lane) {
+                                           const Ranges<SETS>& R, int lane) {
 #pragma unroll
     for (int g = 0; g < PRE; ++g) {
         const int t = (t0 + g < W) ? t0 + g : 0;
@@ -103,7 +107,7 @@ __device__ __forceinline__ void load_batch(Batch<PRE, WIN>& X, const DiffTable& 
     }
 }
 
-template <int PRE, int WIN>
+template <int PRE, int WIN, int SETS>
 __global__ __launch_bounds__(LD_WAVE) void k_merge_sweep(float* __restrict__ w, int64_t n, int32_t nchunk,
                                                          DiffTable tb, int32_t W,
                                                          const int32_t* __restrict__ ctab, float lr) {
@@ -128,9 +132,9 @@ __global__ __launch_bounds__(LD_WAVE) void k_merge_sweep(float* __restrict__ w, 
 
     // lane t: where the records of diffs t and t + 64 lie in this chunk, and the guesses for this sub-tile
     const int32_t chunk = static_cast<int32_t>(sub / kChunkSubs), part = static_cast<int32_t>(sub % kChunkSubs);
-    Ranges R;
+    Ranges<SETS> R;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < SETS; ++h) {
         const int t = h * LD_WAVE + lane;
         R.c0[h] = R.c1[h] = 0;
         if (t < W) {
@@ -264,10 +268,14 @@ extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
         const dim3 grid((nsub + 7) / 8 * 8), wave(LD_WAVE);
         // at most ~16 records per diff and sub-tile: one window per diff is plenty
-        if (gw > 10 && most * kSub <= 16 * n)
-            k_merge_sweep<20, 1><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
-        else
-            k_merge_sweep<10, 2><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
+        const bool thin = gw > 10 && most * kSub <= 16 * n;
+        if (gw <= LD_WAVE) {
+            if (thin) k_merge_sweep<20, 1, 1><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
+            else k_merge_sweep<10, 2, 1><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
+        } else {
+            if (thin) k_merge_sweep<20, 1, 2><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
+            else k_merge_sweep<10, 2, 2><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
+        }
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     }
     return LD_OK;
