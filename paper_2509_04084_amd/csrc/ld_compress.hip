@@ -472,7 +472,10 @@ constexpr int kMainWaves = 1;                                // waves per tile
 constexpr int kMainRows = kTile / (kMainWaves * LD_WAVE * 4);  // float4 rows per lane
 constexpr int kMainWaveTile = LD_WAVE * 4 * kMainRows;      // consecutive elements per wave
 
+// SMALL: the slots have the minimum size (every call at the usual densities): a constant then.
+template <bool SMALL>
 __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __restrict__ g, float* __restrict__ r, Ctx c) {
+    const int32_t slot_size = SMALL ? kSlotMin : c.slot;
     __shared__ uint32_t wtot[kMainWaves];
     // consecutive workgroups go to different XCDs: each XCD streams one contiguous eighth of the tiles
     const int32_t tile = static_cast<int32_t>((blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8);
@@ -547,7 +550,7 @@ __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __re
             btot += x;
         }
     }
-    const bool fits = btot <= static_cast<uint32_t>(c.slot);  // else: the residual keeps r + g everywhere, the slot stays unused
+    const bool fits = btot <= static_cast<uint32_t>(slot_size);  // else: the residual keeps r + g everywhere, the slot stays unused
     if (threadIdx.x == 0) c.cnt[tile] = fits ? btot : kOverflow;
     // residual: +0 where the guessed threshold selects, r + g elsewhere
 #pragma unroll
@@ -561,8 +564,8 @@ __global__ __launch_bounds__(kMainWaves * LD_WAVE) void k_main(const float* __re
             store4(r, t + (j * LD_WAVE + lane) * 4, mask[j], x);
     }
     if (!fits || total == 0) return;
-    float* sv = c.cval + static_cast<int64_t>(tile) * c.slot;
-    uint16_t* si = c.cidx + static_cast<int64_t>(tile) * c.slot;
+    float* sv = c.cval + static_cast<int64_t>(tile) * slot_size;
+    uint16_t* si = c.cidx + static_cast<int64_t>(tile) * slot_size;
 #pragma unroll
     for (int j = 0; j < kMainRows; ++j) {
         if (flag[j] == 0) continue;
@@ -609,6 +612,11 @@ struct Rows {
     static constexpr int kTrips = kTilesPerWave / kTiles;
 };
 
+// Slot size as the candidate passes see it: calls that run them with 16 lanes per tile expect at
+// most 128 candidates per tile and always get the minimum slot, a constant.
+template <int ROW>
+__device__ __forceinline__ int32_t slot_of(const Ctx& c) { return ROW == 16 ? kSlotMin : c.slot; }
+
 __device__ __forceinline__ int wave_in_group() { return static_cast<int>(threadIdx.x >> 6) & (kWaves - 1); }
 
 // Lane u < kTilesPerWave: the candidate count of the wave's tile u (k_main writes a
@@ -654,7 +662,7 @@ __device__ __forceinline__ void trip_fetch(const Ctx& c, int32_t tile0, uint32_t
     const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
     const uint32_t n = (q < R::kTrips && cn <= R::kFast) ? cn : 0u;
     const uint32_t first = static_cast<uint32_t>(lane & (ROW - 1)) * kPerLane;
-    const int64_t at = static_cast<int64_t>(tile0 + u) * c.slot + first;
+    const int64_t at = static_cast<int64_t>(tile0 + u) * slot_of<ROW>(c) + first;
     ld_f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
     ld_u32x4 xi = {0u, 0u, 0u, 0u};
     if (first < n) a = *reinterpret_cast<const ld_f32x4*>(c.cval + at);
@@ -686,7 +694,7 @@ __device__ __forceinline__ void slow_tiles(const Ctx& c, const float* __restrict
         const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
         const bool stored = cn != kOverflow;
         const uint32_t total = stored ? cn : static_cast<uint32_t>(kTile);
-        const int64_t slot = static_cast<int64_t>(tile0 + u) * c.slot;
+        const int64_t slot = static_cast<int64_t>(tile0 + u) * slot_of<ROW>(c);
         const int64_t tbase = tbase0 + static_cast<int64_t>(u) * kTile;
         begin(u);
         // kAhead batches of 64 are requested before the first is handed on: a tile read back from
@@ -1606,12 +1614,14 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (n_group == 0) return LD_OK;
     const dim3 grid(static_cast<uint32_t>(n_group));
-    k_main<<<dim3(static_cast<uint32_t>(n_group * kTilesPerGroup)), dim3(kMainWaves * LD_WAVE), 0, st>>>(grad, residual, c);
+    const dim3 mgrid(static_cast<uint32_t>(n_group * kTilesPerGroup)), mblock(kMainWaves * LD_WAVE);
+    if (slot == kSlotMin) k_main<true><<<mgrid, mblock, 0, st>>>(grad, residual, c);
+    else k_main<false><<<mgrid, mblock, 0, st>>>(grad, residual, c);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (K == 0) return LD_OK;
     const dim3 hgrid(static_cast<uint32_t>((n_group + kHistGroups - 1) / kHistGroups)), hblock(kHistGroups * kThreads);
     // lanes per tile in the candidate passes: enough for the candidates a tile is expected to hold
-    const int row = per_tile <= 128 ? 16 : (per_tile <= 256 ? 32 : 64);
+    const int row = (per_tile <= 128 && slot == kSlotMin) ? 16 : (per_tile <= 256 ? 32 : 64);  // 16 implies the minimum slot
     if (row == 16) k_hist<16><<<hgrid, hblock, 0, st>>>(residual, c);
     else if (row == 32) k_hist<32><<<hgrid, hblock, 0, st>>>(residual, c);
     else k_hist<64><<<hgrid, hblock, 0, st>>>(residual, c);
