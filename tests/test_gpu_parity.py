@@ -192,7 +192,8 @@ def test_merge_flat_window(strategy):
 
 
 @pytest.mark.parametrize("n,W,dens", [(1, 1, 1.0), (4095, 3, 0.5), (4097, 5, 0.02), (1000003, 9, 0.03),
-                                      (300000, 140, 0.004), (123457, 2, 1.0), (50000, 4, 0.0)])
+                                      (300000, 140, 0.004), (123457, 2, 1.0), (50000, 4, 0.0),
+                                      (2000003, 40, 0.0005), (2000003, 100, 0.0004)])
 def test_merge_ragged_and_dense_windows(n, W, dens):
     rs = np.random.RandomState(n % 1000 + W)
     w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
