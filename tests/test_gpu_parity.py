@@ -697,3 +697,88 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
         r_host = er
         # eager work between the replays, on the same buffers' neighbours
         torch.randn(1 << 20, device=DEV).sum().item()
+
+
+# ------------------------------------------------------------ randomised shapes
+
+def _random_case(seed):
+    """Segment table, k per segment, gradient and residual drawn from a mixture of shapes and value laws
+    (tiny to 2.5 M-element segments; k from 0 to n_s; normal, heavy-tailed, quantised, mostly-zero,
+    constant and fp16-rounded values; zero, random or cancelling residual)."""
+    rs = np.random.RandomState(seed)
+    sizes = []
+    for _ in range(int(rs.choice([1, 2, 3, 8, 25]))):
+        u = rs.rand()
+        sizes.append(int(rs.randint(0, 200) if u < 0.25 else rs.randint(200, 70000) if u < 0.6
+                         else rs.randint(70000, 600000) if u < 0.9 else rs.randint(600000, 2500000)))
+    off = synth.seg_offsets(sizes)
+    n = int(off[-1])
+    ks = []
+    for s_ in sizes:
+        u = rs.rand()
+        k_ = (0 if s_ == 0 else max(1, int(np.ceil(s_ * rs.choice([0.001, 0.01, 0.03, 0.1])))) if u < 0.5
+              else int(rs.randint(0, s_ + 1)) if u < 0.7 else s_ if u < 0.8 else 1 if u < 0.9 else 0)
+        ks.append(min(s_, k_))
+    u = rs.rand()
+    if u < 0.35:
+        g = rs.standard_normal(n).astype(np.float32)
+    elif u < 0.5:
+        g = (rs.standard_t(3, n) * 1e-3).astype(np.float32)
+    elif u < 0.65:
+        g = (np.round(rs.standard_normal(n) * rs.choice([2, 8, 64])) / 8).astype(np.float32)
+    elif u < 0.8:
+        g = rs.standard_normal(n).astype(np.float32)
+        g[rs.rand(n) < rs.choice([0.5, 0.9, 0.995])] = 0
+    elif u < 0.9:
+        g = np.full(n, rs.choice([0.0, 1.5, -2.0]), np.float32)
+    else:
+        g = rs.standard_normal(n).astype(np.float32).astype(np.float16).astype(np.float32)
+    r = np.zeros(n, np.float32) if rs.rand() < 0.4 else (rs.standard_normal(n) * 0.3).astype(np.float32)
+    if rs.rand() < 0.2:
+        r = (-g).astype(np.float32)
+    return rs, off, np.array(ks, np.int32), g, r
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_randomised_shapes_against_the_oracle(block):
+    for seed in range(100 * block, 100 * block + 12):
+        rs, off, k, g, r = _random_case(seed)
+        n = int(off[-1])
+        print(f"[random] seed={seed} n={n} n_seg={len(k)} K={int(k.sum())}", flush=True)
+        W = int(rs.choice([1, 2, 5]))
+        idxs, vals, r_ref = [], [], r
+        r_gpu = to_gpu(r)
+        for t in range(W):
+            gt = g if t == 0 else (rs.standard_normal(n) * 0.5).astype(np.float32)
+            oi, ov, r_ref = oracle.topk_ef(gt, r_ref, off, k, select=True)
+            nbytes = ld.ld_compress_topk_workspace(off) if rs.rand() < 0.3 else ld.ld_compress_topk_workspace(off, k)
+            gi, gv = ld.ld_compress_topk(to_gpu(gt), r_gpu, off, k,
+                                         workspace=torch.empty(nbytes, dtype=torch.uint8, device=DEV))
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(gi.cpu().numpy(), oi, err_msg=f"idx seed {seed} t {t}")
+            np.testing.assert_array_equal(bits(gv.cpu().numpy()), bits(ov), err_msg=f"val seed {seed} t {t}")
+            np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(r_ref), err_msg=f"residual seed {seed} t {t}")
+            idxs.append(oi)
+            vals.append(ov)
+        if n == 0:
+            continue
+        w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+        ref = oracle.merge_sparse(w0, idxs, vals, 0.1)
+        for strategy in (ld.LD_MERGE_SWEEP, ld.LD_MERGE_SCATTER):
+            w = to_gpu(w0)
+            ld.ld_merge_sparse(w, [to_gpu(i) for i in idxs], [to_gpu(v) for v in vals], 0.1, strategy=strategy)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref), err_msg=f"merge seed {seed}")
+        z = np.zeros(n, np.float32)
+        wa, ma, va = to_gpu(w0), to_gpu(z), to_gpu(z)
+        ld.ld_merge_sparse_adam(wa, ma, va, [to_gpu(i) for i in idxs], [to_gpu(v) for v in vals], 3, 1e-3, **synth.ADAM)
+        torch.cuda.synchronize()
+        check_adam_close((wa, ma, va), oracle.sparse_adam_replay(w0, z, z, idxs, vals, 3, 1e-3, **synth.ADAM),
+                         f"sparse adam seed {seed}")
+        ci, cv, cn = ld.ld_combine_sparse([to_gpu(i) for i in idxs], [to_gpu(v) for v in vals], n, 1.0)
+        torch.cuda.synchronize()
+        ei, ev = oracle.combine_sparse(idxs, vals, n, 1.0)
+        cnt = int(cn.item())
+        assert cnt == ei.size, f"combine count seed {seed}"
+        np.testing.assert_array_equal(ci[:cnt].cpu().numpy(), ei, err_msg=f"combine idx seed {seed}")
+        np.testing.assert_array_equal(bits(cv[:cnt].cpu().numpy()), bits(ev), err_msg=f"combine val seed {seed}")
