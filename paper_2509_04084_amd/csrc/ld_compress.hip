@@ -16,9 +16,9 @@
 //             T_est (the sample key at the rank that corresponds to k), and the top
 //             of the fine bins that the later passes lay over the keys above tau.
 //             When the whole segment fits in the sample the three are exact.
-//   k_main    the only full pass, 12 bytes per element. One workgroup per
-//             4096-element tile, tiles in address order so that the workgroups in
-//             flight cover one contiguous window of HBM. Elements with key >= tau
+//   k_main    the only full pass, 12 bytes per element. One wave per 4096-element
+//             tile, each XCD walking one contiguous eighth of the tiles in address
+//             order. Elements with key >= tau
 //             go, in index order, into the tile's candidate slot. The residual is
 //             written as if T_est were the threshold: +0 where key >= T_est, r + g
 //             elsewhere - so that the scattered repair writes of the last pass touch
