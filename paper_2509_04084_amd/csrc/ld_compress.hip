@@ -77,7 +77,8 @@ constexpr int kGatherBase = 4096;                 // gather list of a segment: k
 constexpr int kGatherPer = 4096;
 constexpr int kSegPerLaunch = 448;
 constexpr int kFullGrid = 1024;                   // workgroups of the (normally idle) k_full_* kernels
-constexpr uint32_t kModeCand = 0, kModeFull = 1;
+constexpr uint32_t kModeCand = 0, kModeFull = 1, kModeTies = 2;
+constexpr uint32_t kTieSuspect = 512;             // sample keys equal to the candidate threshold (of 16384) that make a segment "tied"
 
 constexpr uint32_t kOverflow = 0xFFFFFFFFu;       // tile count: slot too small, read the residual
 
@@ -99,7 +100,7 @@ struct GroupDesc {      // 64 bytes: all a workgroup needs to know about its gro
     uint32_t tau;       // candidate threshold (see SegState)
     uint32_t sh;        // fine-bin shift
     uint32_t test;      // guessed threshold
-    uint32_t pad;
+    uint32_t tied;      // 1: the key tau - 1 is massively repeated (see SegState::tied)
 };
 
 struct SegState {       // 64 bytes
@@ -108,11 +109,18 @@ struct SegState {       // 64 bytes
     uint32_t test;      // guessed threshold T_est >= tau: k_main stores +0 where key >= T_est
     uint32_t prefix;    // k_bin: threshold bin; k_select: exact threshold T (k_full_*: radix prefix)
     uint32_t krem;      // rank left inside prefix; finally the number of ties to keep
-    uint32_t mode;      // kModeCand | kModeFull
+    uint32_t mode;      // kModeCand | kModeFull | kModeTies
     uint32_t gcount;    // keys gathered from the threshold bin
     uint32_t fdone[4];  // tickets of the full-segment path: level 1, 2, 3, count
     uint32_t kmin, kmax;  // bounds of the threshold-bin keys that found no room in the gather list
-    uint32_t pad[3];
+    // A tied segment: the sample found one key repeated so often (a frozen layer's zeros, a constant)
+    // that taking it as candidate threshold would make nearly every element a candidate. The
+    // candidates are then the keys ABOVE it (tau = that key + 1) and nothing is pre-zeroed. If the
+    // candidates turn out fewer than k, the threshold can only be that key or a smaller one:
+    // k_gather counts the key per tile in the residual, k_select checks that with those ties k is
+    // reached (else: the full path), and k_emit takes the ties in index order (kModeTies).
+    uint32_t tied;
+    uint32_t pad[2];
 };
 
 struct Ctx {
@@ -379,7 +387,7 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
 
     // candidate threshold, guessed threshold and bin width from a sample of |r + g|
     const int64_t ns = end - off;
-    uint32_t tau = 0xFFFFFFFFu, test = 0xFFFFFFFFu, binsh = 0;
+    uint32_t tau = 0xFFFFFFFFu, test = 0xFFFFFFFFu, binsh = 0, tied = 0;
     if (k > 0 && !no_estimate) {
         uint32_t key[kSampleItems];
         uint32_t valid = 0;
@@ -449,7 +457,23 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
                 test = tau + (1u << kShift2);
             } else {
                 test = sel[1];
-                const uint32_t range = (sel[2] | ((1u << kShift2) - 1u)) - tau;
+                // how often does the sample hold the candidate threshold's own key?
+                uint32_t same = 0;
+#pragma unroll
+                for (int i = 0; i < kSampleItems; ++i) same += key[i] == tau;
+                same = ld_wave_sum(same);
+                __syncthreads();
+                if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = same;
+                __syncthreads();
+                same = 0;
+                for (int i = 0; i < kPrepThreads / LD_WAVE; ++i) same += sh[i];
+                if (same >= kTieSuspect && tau != 0xFFFFFFFFu) {
+                    tied = 1;  // candidates: the keys above it; no pre-zeroing (see SegState::tied)
+                    tau += 1;
+                    test = 0xFFFFFFFFu;
+                }
+                const uint32_t top = sel[2] | ((1u << kShift2) - 1u);
+                const uint32_t range = top > tau ? top - tau : 0u;
                 while ((range >> binsh) > static_cast<uint32_t>(kTopBin - 1)) ++binsh;
             }
         }
@@ -460,10 +484,11 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
         c.state[s].sh = binsh;
         c.state[s].test = test;
         c.state[s].kmin = 0xFFFFFFFFu;
+        c.state[s].tied = tied;
     }
     for (int32_t q = threadIdx.x; q < ngroup; q += kPrepThreads)
         c.gdesc[d.group0 + q] = GroupDesc{align_down4(off) + static_cast<int64_t>(q) * kGroup, off, end, d.out0,
-                                          s, k, d.group0, ngroup, tau, binsh, test, 0u};
+                                          s, k, d.group0, ngroup, tau, binsh, test, tied};
 }
 
 // -------------------------------------------------------------------- k_main
@@ -752,7 +777,7 @@ __device__ __forceinline__ GroupRange seg_range(const Ctx& c, int32_t s) {
     r.group0 = d.group0;
     r.ngroup = dn.group0 - d.group0;
     r.out0 = d.out0;
-    r.tau = r.sh = r.test = r.pad = 0;
+    r.tau = r.sh = r.test = r.tied = 0;
     return r;
 }
 
@@ -849,9 +874,31 @@ __global__ __launch_bounds__(kThreads) void k_bin(Ctx c) {
     for (int b = threadIdx.x; b < kBins; b += kThreads) h[b] = 0;  // the full path reuses the row
     if (total >= static_cast<uint32_t>(gr.k)) {
         if (threadIdx.x == 0) { st->prefix = res[0]; st->krem = res[1]; }
+    } else if (st->tied) {
+        // every candidate is selected; the rest must be ties of the repeated key (k_select checks)
+        if (threadIdx.x == 0) {
+            st->mode = kModeTies;
+            st->prefix = st->tau - 1u;                          // T
+            st->krem = static_cast<uint32_t>(gr.k) - total;     // m
+        }
     } else {
         mark_full(c, st, gr, &list0);  // the candidate threshold was too high
     }
+}
+
+// Elements of the tile starting at tbase whose key is `key`, counted by the whole wave from the
+// residual (which holds r + g wherever nothing was zeroed).
+__device__ __forceinline__ uint32_t count_key_in_tile(const float* __restrict__ r, int64_t tbase, int64_t lo,
+                                                      int64_t hi, uint32_t key) {
+    uint32_t n = 0;
+#pragma unroll 4
+    for (int j = 0; j < kTile / (LD_WAVE * 4); ++j) {
+        float x[4];
+        const uint32_t mask = load4(r, tbase + (j * LD_WAVE + ld_lane()) * 4, lo, hi, x);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) n += ((mask >> q) & 1u) && ld_key(x[q]) == key;
+    }
+    return ld_wave_sum(n);
 }
 
 // Keys of the threshold bin held by the lanes of a wave (bit j of `in`: candidate j of the lane)
@@ -901,7 +948,11 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     const uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
     SegState* st = c.state + gr.seg;
-    if (gr.k == 0 || st->mode != kModeCand) return;
+    const uint32_t mode = st->mode;
+    if (gr.k == 0 || mode == kModeFull) return;
+    // kModeTies: every candidate lies above the threshold and nothing is gathered; the ties of a
+    // tile are what k_main counted
+    const bool ties_mode = mode == kModeTies;
     const uint32_t tau = gr.tau, binsh = gr.sh, b1 = st->prefix;
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
@@ -916,6 +967,17 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     bool full = false;
     uint32_t lmin = 0xFFFFFFFFu, lmax = 0;
     uint32_t part_gt = 0, part_eq = 0;  // fast path: the first lane of a row sums the row's tiles
+    uint32_t wave_ties = 0;
+    if (ties_mode) {  // the repeated key tau - 1, counted per tile in the residual
+        const int tl0 = w * kTilesPerWave;
+#pragma unroll 1
+        for (int u = 0; u < kTilesPerWave; ++u) {
+            const int64_t tbase = gr.base + static_cast<int64_t>(tl0 + u) * kTile;
+            const uint32_t t = tbase < gr.hi ? count_key_in_tile(r, tbase, gr.lo, gr.hi, tau - 1u) : 0u;
+            if (lane == 0) c.tile_eq[tile0 + u] = t;
+            wave_ties += t;
+        }
+    }
     Trip Q, N;
     trip_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
@@ -926,8 +988,8 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
         for (int j = 0; j < kPerLane; ++j) {
             const uint32_t bin = fine_bin(ld_key(Q.v[j]), tau, binsh);
             const bool valid = static_cast<uint32_t>(j) < Q.have;
-            cnt += valid && bin > b1;
-            in |= static_cast<uint32_t>(valid && bin == b1) << j;
+            cnt += valid && (ties_mode || bin > b1);
+            in |= static_cast<uint32_t>(valid && !ties_mode && bin == b1) << j;
         }
         const uint32_t n_in = __popc(in);
         const uint64_t who = __ballot(in != 0);
@@ -960,7 +1022,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
         const uint32_t eqc = both >> 16;
         if ((lane & (ROW - 1)) == 0 && Q.cn <= Rows<ROW>::kFast) {
             c.tile_gt[tile0 + Q.u] = cnt;
-            c.tile_eq[tile0 + Q.u] = eqc;  // keys in the threshold bin; k_select takes out those that are not T
+            if (!ties_mode) c.tile_eq[tile0 + Q.u] = eqc;  // keys in the threshold bin; k_select takes out those that are not T
             part_gt += cnt;
             part_eq += eqc;
         }
@@ -978,8 +1040,8 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
         [&](bool have, float v, uint32_t, bool) {
             const uint32_t key = ld_key(v);
             const uint32_t bin = have ? fine_bin(key, tau, binsh) : 0u;
-            gt += __popcll(__ballot(have && bin > b1));
-            const bool in = have && bin == b1;
+            gt += __popcll(__ballot(have && (ties_mode || bin > b1)));
+            const bool in = have && !ties_mode && bin == b1;
             const uint64_t min_ = __ballot(in);
             if (min_) {
                 const uint32_t total = static_cast<uint32_t>(__popcll(min_));
@@ -1005,7 +1067,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
         [&](int u) {
             if (lane == 0) {
                 c.tile_gt[tile0 + u] = gt;
-                c.tile_eq[tile0 + u] = eq;
+                if (!ties_mode) c.tile_eq[tile0 + u] = eq;
             }
             slow_gt += gt;
             slow_eq += eq;
@@ -1023,7 +1085,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
         }
     }
     const uint32_t wave_gt = ld_wave_sum(part_gt) + slow_gt;
-    const uint32_t wave_eq = ld_wave_sum(part_eq) + slow_eq;
+    const uint32_t wave_eq = ld_wave_sum(part_eq) + slow_eq + wave_ties;
     if (lane == 0) {
         wsum[0][w] = wave_gt;
         wsum[1][w] = wave_eq;
@@ -1047,14 +1109,18 @@ __global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
     __shared__ uint32_t list0;
     const GroupRange gr = seg_range(c, blockIdx.x);
     SegState* st = c.state + gr.seg;
-    if (gr.k == 0 || gr.ngroup == 0 || st->mode != kModeCand) return;
+    const uint32_t mode = st->mode;
+    if (gr.k == 0 || gr.ngroup == 0 || mode == kModeFull) return;
     const uint32_t ng = st->gcount;
     const uint32_t* gkey = c.gkey + gather_first(gr.seg, gr.lo);
     const int32_t* gtile = c.gtile + gather_first(gr.seg, gr.lo);
     const uint32_t gcap = gather_cap(gr.lo, gr.hi);
     uint32_t T, m;
     uint32_t seen = 0;
-    if (ng > gcap) {
+    if (mode == kModeTies) {  // k_bin has found both: nothing to select
+        T = st->prefix;
+        m = st->krem;
+    } else if (ng > gcap) {
         // More keys in the threshold bin than the list holds. If they are all one value (massive
         // ties: a frozen layer's zeros, values on a coarse grid) nothing has to be selected among
         // them: T is that value, and the rank left inside the bin is the number of ties to keep,
@@ -1143,6 +1209,10 @@ __global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
         carry_eq += te;
         carry_out += tg;
     }
+    if (mode == kModeTies && carry_eq < m) {
+        mark_full(c, st, gr, &list0);  // the repeated key does not fill k either: the threshold lies below it
+        return;
+    }
     if (threadIdx.x == 0) { st->prefix = T; st->krem = m; }
 }
 
@@ -1153,15 +1223,16 @@ __global__ __launch_bounds__(kThreads) void k_select(Ctx c) {
 template <int ROW>
 __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_t* __restrict__ out_idx,
                                                    float* __restrict__ out_val, Ctx c) {
-    __shared__ uint32_t tile_out[kTilesPerGroup], tile_eqb[kTilesPerGroup];
+    __shared__ uint32_t tile_out[kTilesPerGroup], tile_eqb[kTilesPerGroup], tile_take[kTilesPerGroup];
     constexpr int kTiles = Rows<ROW>::kTiles;
     constexpr uint32_t kFast = Rows<ROW>::kFast;
     __shared__ int32_t stage_i[kWaves][kTiles * kFast];
     __shared__ float stage_v[kWaves][kTiles * kFast];
-    const uint32_t mycnt = wave_counts(c, blockIdx.x);
+    uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
     const SegState* st = c.state + gr.seg;
     if (gr.k == 0) return;
+    const uint32_t mode = st->mode;
     const uint32_t tau = gr.tau, test = gr.test, T = st->prefix, m = st->krem;
     const int lane = ld_lane();
     const int w = threadIdx.x >> 6;
@@ -1169,7 +1240,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     const int32_t tile0 = blockIdx.x * kTilesPerGroup + tl0;
     int64_t tbase = 0;
     Trip Q, N;
-    if (st->mode != kModeCand) {
+    if (mode == kModeFull) {
         trip_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
         for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
@@ -1197,8 +1268,14 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
         const uint32_t take = umin(eq_before + ce, m) - umin(eq_before, m);
         tile_out[lane] = c.group_gt[blockIdx.x] + ld_wave_iscan(cg + take) - (cg + take);
         tile_eqb[lane] = eq_before;
+        tile_take[lane] = take;
     }
     __syncthreads();
+    // kModeTies: the ties are not among the stored candidates. A tile that keeps some of them is
+    // read back from the residual (nothing was pre-zeroed in a tied segment), where candidates and
+    // ties come in index order; keys at or above T pass the filter there.
+    const uint32_t keep_from = mode == kModeTies ? T : tau;
+    if (mode == kModeTies && lane < kTilesPerWave && tile_take[tl0 + lane] > 0) mycnt = kOverflow;
     trip_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
 #pragma unroll 1
     for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
@@ -1255,7 +1332,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     uint32_t run_out = 0;  // records of the segment emitted before this point
     uint32_t run_eq = 0;   // ties seen before this point
     slow_tiles<true, ROW>(
-        c, r, gr, blockIdx.x, mycnt, tau,
+        c, r, gr, blockIdx.x, mycnt, keep_from,
         [&](int u) {
             run_out = tile_out[tl0 + u];
             run_eq = tile_eqb[tl0 + u];
