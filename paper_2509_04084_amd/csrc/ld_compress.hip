@@ -42,6 +42,10 @@
 //     unless the overfull bin holds one value only (massive ties: zeros of a frozen
 //     layer, values on a grid): then that value is the threshold and its ties are
 //     taken in index order without leaving the candidate path.
+//   * a segment whose sample holds the candidate threshold's own key hundreds of times (a
+//     frozen layer's zeros, a constant) is "tied": its candidates are the keys above that
+//     key, nothing is pre-zeroed, and if they are fewer than k the repeated key is the
+//     threshold; its ties are counted per tile and taken in index order from the residual.
 // The slot size (256 .. 2048 candidates per tile) and the lanes per tile of the candidate
 // passes (16, 32 or 64) are chosen per call from the densities seg_k / n_s, so that calls
 // at 5 or 10 % keep the same structure (the paper varies rho from 0.001 to 0.1, Exp. 10).
