@@ -131,6 +131,42 @@ def test_compress_massive_ties_at_the_threshold():
                    synth.seg_topk(sizes, 1, 100), tag="values on a grid")
 
 
+def test_compress_tied_segment_with_and_without_enough_ties():
+    # A segment is treated as "tied" when the 16 K-element sample holds the candidate threshold's
+    # own key hundreds of times. White-box: the sample positions are rebuilt here (256 jittered runs
+    # of 64 elements), so that the sample can be made to see a repeated key X at the threshold.
+    # (a) the rest of the segment holds X often enough: X is the threshold, ties by index;
+    # (b) it does not: the tied guess is wrong, the threshold lies below X, full-segment path.
+    ns, k_s, X = 2_000_000, 20_000, np.float32(0.5)
+    stride = ns // 256
+    pos = []
+    for run in range(256):
+        x = (run * 2654435761) & 0xFFFFFFFF
+        x ^= x >> 16
+        x = (x * 0x7FEB352D) & 0xFFFFFFFF
+        x ^= x >> 15
+        x = (x * 0x846CA68B) & 0xFFFFFFFF
+        x ^= x >> 16
+        pos.append(run * stride + ((x * (stride - 63)) >> 32) + np.arange(64))
+    pos = np.concatenate(pos)
+    rs = np.random.RandomState(23)
+    sign = lambda m: np.where(rs.rand(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    base = (rs.uniform(0.0, 0.4, ns).astype(np.float32) * sign(ns))
+    picked = rs.permutation(pos)
+    base[picked[:200]] = rs.uniform(2.0, 3.0, 200).astype(np.float32) * sign(200)
+    base[picked[200:800]] = X * sign(600)
+    off = np.array([0, ns], np.int64)
+    k = np.array([k_s], np.int32)
+    z = np.zeros(ns, np.float32)
+    few = base.copy()                                  # (b): 800 elements reach X, k is 20,000
+    check_compress(few, z, off, k, tag="tied guess, too few ties", strategies=(ld.LD_COMPRESS_AUTO,))
+    many = base.copy()                                 # (a): 25,000 more copies of +-X elsewhere
+    rest = np.setdiff1d(np.arange(ns), pos)
+    many[rs.choice(rest, 25_000, replace=False)] = X * sign(25_000)
+    oi, ov, _ = check_compress(many, z, off, k, tag="tied guess, enough ties", strategies=(ld.LD_COMPRESS_AUTO,))
+    assert np.count_nonzero(np.abs(ov) == X) == k_s - 200 and np.count_nonzero(np.abs(ov) > X) == 200
+
+
 def test_compress_resnet50_shape():
     wl = synth.workload("resnet50")
     g = synth.gradient(wl, 0).numpy()
