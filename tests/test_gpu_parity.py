@@ -818,3 +818,33 @@ def test_randomised_shapes_against_the_oracle(block):
         assert cnt == ei.size, f"combine count seed {seed}"
         np.testing.assert_array_equal(ci[:cnt].cpu().numpy(), ei, err_msg=f"combine idx seed {seed}")
         np.testing.assert_array_equal(bits(cv[:cnt].cpu().numpy()), bits(ev), err_msg=f"combine val seed {seed}")
+
+
+def test_randomised_dense_replays_against_the_oracle():
+    rs = np.random.RandomState(77)
+    for case in range(16):
+        n = int(rs.choice([1, 3, 4095, 4096, 4097, 65537, 300001, 1500000]))
+        W = int(rs.randint(1, 10))
+        step0 = int(rs.choice([0, 1, 7, 1000, 123456]))
+        hp = dict(lr=float(10.0 ** rs.uniform(-5, -2)), beta1=float(rs.choice([0.0, 0.8, 0.9])),
+                  beta2=float(rs.choice([0.9, 0.99, 0.999])), eps=float(rs.choice([1e-8, 1e-6])))
+        print(f"[random dense] case={case} n={n} W={W} step0={step0} {hp}", flush=True)
+        w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+        m0 = (rs.standard_normal(n) * 1e-3).astype(np.float32)
+        v0 = (rs.standard_normal(n) ** 2 * 1e-6).astype(np.float32)
+        scale = float(10.0 ** rs.uniform(-4, 0))
+        grads = [torch.from_numpy((rs.standard_normal(n) * scale).astype(np.float32)).to(torch.bfloat16) for _ in range(W)]
+        gbits = [g.view(torch.int16).numpy().view(np.uint16) for g in grads]
+        src = [g.to(DEV) for g in grads]
+        snaps = [torch.empty_like(s) for s in src]
+        if case % 2:
+            ld.ld_snapshot_layers(src, snaps)
+        else:
+            for a, b in zip(src, snaps):
+                ld.ld_snapshot_layer(a, b)
+        w, m, v = to_gpu(w0), to_gpu(m0), to_gpu(v0)
+        ld.ld_merge_dense_adam(w, m, v, snaps, step0, **hp)
+        torch.cuda.synchronize()
+        for s_, b_ in zip(snaps, gbits):
+            np.testing.assert_array_equal(s_.cpu().view(torch.int16).numpy().view(np.uint16), b_)
+        check_adam_close((w, m, v), oracle.adam_replay(w0, m0, v0, gbits, step0, **hp), f"case {case}")
