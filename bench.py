@@ -132,6 +132,31 @@ class SparseLeg:
         torch.cuda.synchronize()
         return float(np.mean(tm.ms()["combine"][1:])), total, int(cnt.item())
 
+    # -- next row: the window's diffs in page-locked host memory, merged as they arrive (pipelined
+    #    recovery); wall-clock from the first copy to the end of the last merge
+    def time_recovery_from_host(self, group=5, reps=2):
+        hi = [torch.empty(t.shape, dtype=t.dtype, pin_memory=True).copy_(t) for t in self.idx]
+        hv = [torch.empty(t.shape, dtype=t.dtype, pin_memory=True).copy_(t) for t in self.val]
+        K = np.array([t.numel() for t in hi], dtype=np.int64)
+        lib = ld.load()
+        out = {}
+        cs, ms = torch.cuda.Stream(), torch.cuda.Stream()
+        for name, g in (("pipelined", group), ("copy_then_merge", min(self.W, 64))):
+            staging = torch.empty(int(lib.ld_merge_sparse_from_host_staging(K.ctypes.data, self.W, g)),
+                                  dtype=torch.uint8, device=self.dev)
+            times = []
+            for _ in range(reps + 1):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ld.ld_merge_sparse_from_host(self.w, hi, hv, self.wl.lr, group=g, staging=staging,
+                                             copy_stream=cs, merge_stream=ms)
+                cs.synchronize()
+                ms.synchronize()
+                times.append((time.perf_counter() - t0) * 1e3)
+            out[name] = float(np.mean(times[1:]))
+            del staging
+        return out, int(8 * K.sum())
+
     def bytes_sparse_adam(self):
         return 24 * self.n + 8 * self.K * self.W
 
@@ -394,6 +419,14 @@ def main():
                          "frac": nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "note": "8 B per input record + 8 B per output record"},
             "note": "8 of the window's diffs taken as 8 workers' lists; not part of `value`"}
+        rec, nb = sparse.time_recovery_from_host()
+        log(f"[next row] ld_merge_sparse_from_host: {rec['pipelined']:.1f} ms pipelined, "
+            f"{rec['copy_then_merge']:.1f} ms copy-then-merge ({nb / 1e6:.0f} MB of records over the host link)")
+        next_rows["ld_merge_sparse_from_host"] = {
+            "ms": rec["pipelined"], "ms_copy_then_merge": rec["copy_then_merge"], "record_bytes": nb,
+            "host_link_GBps": nb / (rec["pipelined"] * 1e-3) / 1e9,
+            "note": "the window's 20 diffs in page-locked host memory, copied in groups of 5 on one stream while "
+                    "the previous group is merged on another; wall-clock; bound by the host link; not part of `value`"}
     if dense and not args.no_next_rows:
         ms, nb = dense.time_snapshot_to_host()
         log(f"[next row] ld_snapshot_layer into pinned host memory: {ms:.2f} ms for {nb / 1e6:.0f} MB")

@@ -169,6 +169,35 @@ ld_status ld_merge_sparse(float* w, int64_t n,
                           void* workspace, size_t workspace_bytes, ld_stream stream);
 
 /* ------------------------------------------------------------------------
+ * ld_merge_sparse_from_host - ld_merge_sparse for diffs that still lie in host
+ * memory, pipelined (pipelined recovery module, Sec. VI-C: while one
+ * differential checkpoint is merged the next ones are already being read).
+ * The diffs are copied to the device in groups of `group` on copy_stream and
+ * each group is merged on merge_stream while the next one is copied; two
+ * staging slots alternate.  The result is bit for bit that of one
+ * ld_merge_sparse call with the same diffs in the same order.
+ *
+ *   host_idx, host_val  host arrays of W HOST pointers (int32[K[t]], fp32[K[t]]);
+ *              page-locked memory for the copies to overlap; they must stay
+ *              valid and unchanged until copy_stream has passed the call
+ *   group      1 <= group <= 64: diffs per stage (a larger group means fewer
+ *              passes over w and a longer wait before the first merge)
+ *   staging    dev, 256-byte aligned, ld_merge_sparse_from_host_staging() bytes
+ *   workspace  dev, 256-byte aligned, ld_merge_sparse_workspace(n, group, K) bytes
+ *   copy_stream, merge_stream  may be the same stream (then nothing overlaps).
+ *              w is ready when merge_stream has passed the call.
+ * The call creates and destroys four HIP events; it allocates no memory.
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_WORKSPACE, LD_ERR_HIP.
+ */
+size_t    ld_merge_sparse_from_host_staging(const int64_t* K /* host */, int32_t W, int32_t group);
+ld_status ld_merge_sparse_from_host(float* w, int64_t n,
+                                    const int32_t* const* host_idx, const float* const* host_val,
+                                    const int64_t* K, int32_t W, float lr, int32_t group,
+                                    void* staging, size_t staging_bytes,
+                                    void* workspace, size_t workspace_bytes,
+                                    ld_stream copy_stream, ld_stream merge_stream);
+
+/* ------------------------------------------------------------------------
  * ld_check_diff - does a differential that was read back from storage meet
  * what the merges take for granted?  (Recovery loop of Algorithm 1, Sec. IV-B:
  * differentials are loaded from storage and then merged.)  Counts, over the K

@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblowdiff.so")
-SOURCES = ["ld_api.hip", "ld_config.hip", "ld_merge_sparse.hip", "ld_check_diff.hip", "ld_merge_sparse_adam.hip", "ld_combine_sparse.hip", "ld_dense.hip", "ld_compress.hip"]
+SOURCES = ["ld_api.hip", "ld_config.hip", "ld_merge_sparse.hip", "ld_recover.hip", "ld_check_diff.hip", "ld_merge_sparse_adam.hip", "ld_combine_sparse.hip", "ld_dense.hip", "ld_compress.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

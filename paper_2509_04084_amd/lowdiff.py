@@ -48,6 +48,10 @@ def load() -> ctypes.CDLL:
     lib.ld_status_string.restype = ctypes.c_char_p
     lib.ld_compress_topk_workspace.argtypes = [i32, vp]
     lib.ld_compress_topk_workspace.restype = sz
+    lib.ld_merge_sparse_from_host_staging.argtypes = [vp, i32, i32]
+    lib.ld_merge_sparse_from_host_staging.restype = sz
+    lib.ld_merge_sparse_from_host.argtypes = [vp, i64, vp, vp, vp, i32, f32, i32, vp, sz, vp, sz, vp, vp]
+    lib.ld_merge_sparse_from_host.restype = i32
     lib.ld_check_diff.argtypes = [vp, vp, i64, i64, vp, vp]
     lib.ld_check_diff.restype = i32
     lib.ld_compress_topk_workspace_for.argtypes = [i32, vp, vp]
@@ -235,6 +239,39 @@ def ld_merge_dense_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grads
                                     ctypes.c_float(lr), ctypes.c_float(beta1), ctypes.c_float(beta2),
                                     ctypes.c_float(eps), _stream(stream))
     _check("ld_merge_dense_adam", st)
+
+
+def ld_merge_sparse_from_host(w: torch.Tensor, idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], lr: float,
+                              group: int = 4, staging: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None, copy_stream=None,
+                              merge_stream=None) -> None:
+    """ld_merge_sparse for diffs in (pinned) host tensors: groups of `group` diffs are copied on
+    `copy_stream` while the previous group is merged on `merge_stream` (default: the current stream
+    for both, i.e. no overlap). The host tensors must stay alive until the copies are done."""
+    lib = load()
+    W = len(idx)
+    if len(val) != W:
+        raise ValueError("idx and val differ in length")
+    for i, v in zip(idx, val):
+        if i.is_cuda or v.is_cuda or i.dtype != torch.int32 or v.dtype != torch.float32 \
+                or not i.is_contiguous() or not v.is_contiguous() or i.numel() != v.numel():
+            raise TypeError("host diffs: contiguous CPU int32 / float32 tensors of equal length expected")
+    K = np.array([t.numel() for t in idx], dtype=np.int64)
+    n = w.numel()
+    group = max(1, min(int(group), 64))
+    if staging is None:
+        staging = torch.empty(max(256, int(lib.ld_merge_sparse_from_host_staging(_hp(K), W, group))),
+                              dtype=torch.uint8, device=w.device)
+    if workspace is None:
+        workspace = torch.empty(max(256, int(lib.ld_merge_sparse_workspace(n, min(group, max(W, 1)), _hp(K)))),
+                                dtype=torch.uint8, device=w.device)
+    ip = (ctypes.c_void_p * max(W, 1))(*[t.data_ptr() for t in idx])
+    vp = (ctypes.c_void_p * max(W, 1))(*[t.data_ptr() for t in val])
+    st = lib.ld_merge_sparse_from_host(_dev(w, torch.float32, "w"), n, ip, vp, _hp(K), W, ctypes.c_float(lr), group,
+                                       _dev(staging, torch.uint8, "staging"), staging.numel(),
+                                       _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                       _stream(copy_stream), _stream(merge_stream))
+    _check("ld_merge_sparse_from_host", st)
 
 
 def ld_check_diff(idx: torch.Tensor, val: Optional[torch.Tensor], n: int,

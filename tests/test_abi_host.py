@@ -118,6 +118,27 @@ def test_merge_sparse_argument_errors():
     assert call(W=0) == 0 and call(n=0, K=np.array([0, 0], np.int64)) == 0
 
 
+def test_merge_from_host_argument_errors():
+    lib = ld.load()
+    V = ctypes.c_void_p
+    K = np.array([10, 0, 5], np.int64)
+    hp = (ctypes.c_void_p * 3)(FAKE, FAKE, FAKE)
+    stg = lib.ld_merge_sparse_from_host_staging(_p(K), 3, 2)
+    assert stg == 2 * 2 * 256                                  # two slots, one diff of <= 256 B (idx + val) each... the larger group
+    assert lib.ld_merge_sparse_from_host_staging(_p(K), 3, 0) == 0
+    assert lib.ld_merge_sparse_from_host_staging(_p(K), 3, 65) == 0
+
+    def call(w=FAKE, n=100, hi=hp, hv=hp, K=K, W=3, group=2, stg_p=FAKE, stg_b=stg, ws=FAKE, wsb=1 << 20):
+        return lib.ld_merge_sparse_from_host(V(w), n, hi, hv, _p(K), W, ctypes.c_float(0.1), group, V(stg_p), stg_b,
+                                             V(ws), wsb, V(0), V(0))
+
+    assert call(w=0) == -1 and call(hi=None) == -1
+    assert call(group=0) == -2 and call(group=65) == -2 and call(n=2 ** 31) == -2
+    assert call(K=np.array([10, 101, 5], np.int64)) == -2      # more records than elements
+    assert call(stg_p=0) == -3 and call(stg_b=stg - 1) == -3 and call(ws=0) == -3 and call(wsb=8) == -3
+    assert call(W=0) == 0 and call(n=0) == 0
+
+
 def test_dense_argument_errors():
     lib = ld.load()
     V = ctypes.c_void_p

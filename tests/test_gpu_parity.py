@@ -585,6 +585,42 @@ def test_snapshot_into_pinned_host_memory():
         assert torch.equal(b.view(torch.int16), a.cpu().view(torch.int16))
 
 
+# ------------------------------------------------------------ pipelined recovery
+
+@pytest.mark.parametrize("group", [1, 2, 3, 64])
+def test_merge_from_pinned_host_equals_the_window_merge(group):
+    # diffs in page-locked host memory, copied group by group on one stream while the previous
+    # group is merged on another: same bits as the one-call merge and as the oracle
+    n, W = 3_000_001, 7
+    rs = np.random.RandomState(41 + group)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    idxs, vals = [], []
+    for t in range(W):
+        kk = [30_000, 0, 45_000, 1, 30_000, 60_000, 29_999][t]
+        idxs.append(np.sort(rs.choice(n, kk, replace=False)).astype(np.int32))
+        vals.append(rs.standard_normal(kk).astype(np.float32))
+    ref = oracle.merge_sparse(w0, idxs, vals, 0.1)
+    hi = [torch.from_numpy(i).pin_memory() for i in idxs]
+    hv = [torch.from_numpy(v).pin_memory() for v in vals]
+    copy_s, merge_s = torch.cuda.Stream(), torch.cuda.Stream()
+    w = to_gpu(w0)
+    torch.cuda.synchronize()
+    ld.ld_merge_sparse_from_host(w, hi, hv, 0.1, group=group, copy_stream=copy_s, merge_stream=merge_s)
+    merge_s.synchronize()
+    copy_s.synchronize()
+    np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref))
+    # both roles on the current stream, twice in a row with the same staging buffers
+    w2 = to_gpu(w0)
+    K = [i.numel() for i in hi]
+    staging = torch.empty(max(256, ld.load().ld_merge_sparse_from_host_staging(
+        np.array(K, np.int64).ctypes.data_as(__import__("ctypes").c_void_p), W, min(group, W))), dtype=torch.uint8, device=DEV)
+    for _ in range(2):
+        w2.copy_(to_gpu(w0))
+        ld.ld_merge_sparse_from_host(w2, hi, hv, 0.1, group=group, staging=staging)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(w2.cpu().numpy()), bits(ref))
+
+
 # ------------------------------------------------- workspaces hold anything on entry
 
 @pytest.mark.parametrize("fill", [0x00, 0xFF, 0x5A, "random"])
