@@ -23,7 +23,9 @@
  *   ld_merge_sparse_adam Recovery loop of Algorithm 1 with the paper's own update:
  *                        sparse diffs decompressed and merged through Adam into
  *                        model and optimizer state.
- * and ld_check_diff, which counts what is wrong with a diff before it is merged.
+ * and two helpers of the recovery path: ld_merge_sparse_from_host (the merge fed
+ * from page-locked host memory, copies and merges pipelined) and ld_check_diff
+ * (counts what is wrong with a diff before it is merged).
  *
  * General conventions
  *   - Pointers marked "dev" are device (HBM) addresses of the current HIP
