@@ -461,19 +461,31 @@ __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__
                 test = tau + (1u << kShift2);
             } else {
                 test = sel[1];
-                // how often does the sample hold the candidate threshold's own key?
-                uint32_t same = 0;
+                // How often does the sample hold the candidate threshold's own key? (The selected keys
+                // are rounded down to 2^kShift2: look at the sample keys of that bucket; if they are
+                // many and all one value, that value is massively repeated in the segment.)
+                uint32_t same = 0, kmin = 0xFFFFFFFFu, kmax = 0;
 #pragma unroll
-                for (int i = 0; i < kSampleItems; ++i) same += key[i] == tau;
+                for (int i = 0; i < kSampleItems; ++i) {
+                    if ((key[i] >> kShift2) == (tau >> kShift2)) {
+                        ++same;
+                        kmin = umin(kmin, key[i]);
+                        kmax = key[i] > kmax ? key[i] : kmax;
+                    }
+                }
+                __syncthreads();
+                if (threadIdx.x == 0) { res[0] = 0; res[1] = 0xFFFFFFFFu; res[2] = 0; }
+                __syncthreads();
                 same = ld_wave_sum(same);
+                if ((threadIdx.x & 63) == 0 && same) atomicAdd(&res[0], same);
+                if (kmin <= kmax) {
+                    atomicMin(&res[1], kmin);
+                    atomicMax(&res[2], kmax);
+                }
                 __syncthreads();
-                if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = same;
-                __syncthreads();
-                same = 0;
-                for (int i = 0; i < kPrepThreads / LD_WAVE; ++i) same += sh[i];
-                if (same >= kTieSuspect && tau != 0xFFFFFFFFu) {
+                if (res[0] >= kTieSuspect && res[1] == res[2] && res[1] != 0x7FFFFFFFu) {
                     tied = 1;  // candidates: the keys above it; no pre-zeroing (see SegState::tied)
-                    tau += 1;
+                    tau = res[1] + 1u;
                     test = 0xFFFFFFFFu;
                 }
                 const uint32_t top = sel[2] | ((1u << kShift2) - 1u);

@@ -137,7 +137,7 @@ def test_compress_tied_segment_with_and_without_enough_ties():
     # of 64 elements), so that the sample can be made to see a repeated key X at the threshold.
     # (a) the rest of the segment holds X often enough: X is the threshold, ties by index;
     # (b) it does not: the tied guess is wrong, the threshold lies below X, full-segment path.
-    ns, k_s, X = 2_000_000, 20_000, np.float32(0.5)
+    ns, k_s, X = 2_000_000, 20_000, np.float32(0.3)   # a key whose low mantissa bits are not zero
     stride = ns // 256
     pos = []
     for run in range(256):
@@ -151,7 +151,7 @@ def test_compress_tied_segment_with_and_without_enough_ties():
     pos = np.concatenate(pos)
     rs = np.random.RandomState(23)
     sign = lambda m: np.where(rs.rand(m) < 0.5, 1.0, -1.0).astype(np.float32)
-    base = (rs.uniform(0.0, 0.4, ns).astype(np.float32) * sign(ns))
+    base = (rs.uniform(0.0, 0.25, ns).astype(np.float32) * sign(ns))
     picked = rs.permutation(pos)
     base[picked[:200]] = rs.uniform(2.0, 3.0, 200).astype(np.float32) * sign(200)
     base[picked[200:800]] = X * sign(600)
