@@ -449,6 +449,9 @@ def main():
                 "note": "per call of the entry point (all its kernels), HIP events on the launch stream; "
                         "traffic = HBM bytes per call from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by "
                         "what the same counter reads for a 1 GiB plain copy (profiles/)"}
+    if dense:
+        # the layer snapshots are plain copies: what a copy kernel reaches on this machine in this run
+        roofline["plain_copy_GBps"] = calls["ld_snapshot_layers(x34)"]["achieved_GBps"]
     out = {
         "metric": "diff-build GB/s + merge GB/s (grad bytes), % of MI355X HBM roofline",
         "value": value, "unit": "GB/s (gradient bytes)", "n_gpus": 1, "steps": args.steps,
@@ -456,7 +459,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "+".join(x for x in (args.sparse if sparse else None,
                                                     args.dense if dense else None) if x),
-                   "sparse": (f"{args.sparse}: n={sparse.n} segs={len(sparse.wl.sizes)} rho=1% W={sparse.W} "
+                   "sparse": (f"{args.sparse}: n={sparse.n} segs={len(sparse.wl.sizes)} "
+                              f"rho={100.0 * sparse.wl.rho[0] / sparse.wl.rho[1]:g}% W={sparse.W} "
                               f"chained compress + window merge") if sparse else None,
                    "dense": (f"{args.dense}: n={dense.n} layers={len(dense.wl.sizes)} W={dense.W} "
                              f"snapshots per model layer ({len(dense.groups)} calls) + fused Adam replay") if dense else None},

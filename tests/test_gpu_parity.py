@@ -771,6 +771,57 @@ def test_calls_can_be_captured_in_a_graph_and_replayed():
         torch.randn(1 << 20, device=DEV).sum().item()
 
 
+# ------------------------------------------------------------ two streams
+
+def test_independent_calls_on_two_streams_do_not_interfere():
+    # The library keeps no state between calls and works only in the buffers it is handed: two
+    # pipelines (chained compress calls, then the window merge), each with buffers and workspaces of
+    # its own, enqueued alternately on two streams so that their kernels overlap on the GPU, must
+    # each give what the oracle gives for it alone.
+    T = 3
+    cases = []
+    for seed, sizes, rho in ((5, [1_500_000, 70_001, 2_300_000, 4096, 900_000, 3], (1, 100)),
+                             (6, [65_537, 3_100_000, 0, 1_000_000, 131_072], (3, 100))):
+        rs = np.random.RandomState(seed)
+        off = synth.seg_offsets(sizes)
+        k = synth.seg_topk(sizes, *rho) * (np.array(sizes) > 0)
+        n, K = int(off[-1]), int(k.sum())
+        case = dict(
+            off=off, k=k, n=n, K=K, lr=0.1 * (seed - 4),
+            g=[(rs.standard_t(3, n) * 1e-3).astype(np.float32) for _ in range(T)],
+            r0=(rs.standard_normal(n) * 1e-4).astype(np.float32),
+            w0=synth.base_weights(n).numpy() * np.float32(seed),
+            stream=torch.cuda.Stream())
+        case["g_gpu"] = [to_gpu(x) for x in case["g"]]
+        case["r_gpu"] = to_gpu(case["r0"])
+        case["w_gpu"] = to_gpu(case["w0"])
+        case["idx"] = [torch.empty(K, dtype=torch.int32, device=DEV) for _ in range(T)]
+        case["val"] = [torch.empty(K, dtype=torch.float32, device=DEV) for _ in range(T)]
+        case["ws_c"] = torch.empty(ld.ld_compress_topk_workspace(off, k), dtype=torch.uint8, device=DEV)
+        case["ws_m"] = torch.empty(ld.ld_merge_sparse_workspace(n, [K] * T), dtype=torch.uint8, device=DEV)
+        cases.append(case)
+    torch.cuda.synchronize()
+    for t in range(T):
+        for c in cases:
+            ld.ld_compress_topk(c["g_gpu"][t], c["r_gpu"], c["off"], c["k"], c["idx"][t], c["val"][t], c["ws_c"],
+                                stream=c["stream"])
+    for c in cases:
+        ld.ld_merge_sparse(c["w_gpu"], c["idx"], c["val"], c["lr"], c["ws_m"], stream=c["stream"])
+    torch.cuda.synchronize()
+    for j, c in enumerate(cases):
+        r = c["r0"]
+        idxs, vals = [], []
+        for t in range(T):
+            oi, ov, r = oracle.topk_ef(c["g"][t], r, c["off"], c["k"], select=True)
+            np.testing.assert_array_equal(c["idx"][t].cpu().numpy(), oi, err_msg=f"pipeline {j} idx t={t}")
+            np.testing.assert_array_equal(bits(c["val"][t].cpu().numpy()), bits(ov), err_msg=f"pipeline {j} val t={t}")
+            idxs.append(oi)
+            vals.append(ov)
+        np.testing.assert_array_equal(bits(c["r_gpu"].cpu().numpy()), bits(r), err_msg=f"pipeline {j} residual")
+        w = oracle.merge_sparse(c["w0"], idxs, vals, c["lr"])
+        np.testing.assert_array_equal(bits(c["w_gpu"].cpu().numpy()), bits(w), err_msg=f"pipeline {j} w")
+
+
 # ------------------------------------------------------------ randomised shapes
 
 def _random_case(seed):
