@@ -25,22 +25,15 @@
 
 namespace {
 
-#ifndef LD_CB_SUB
-#define LD_CB_SUB 8192
-#endif
-constexpr int kSub = LD_CB_SUB;                 // elements per wave sub-tile
+constexpr int kSub = 8192;                 // elements per wave sub-tile
 constexpr int kChunkSubs = static_cast<int>(kChunk / kSub);  // sub-tiles per chunk of the range table
 static_assert(static_cast<int64_t>(kSub) * kChunkSubs == kChunk, "sub-tiles must tile a chunk");
-#ifndef LD_CB_WIN
-#define LD_CB_WIN 3
-#endif
-constexpr int kWin = LD_CB_WIN;                    // 64-record windows per list loaded ahead
+constexpr int kWin = 3;                    // 64-record windows per list loaded ahead
 constexpr int kPre = 8;                    // lists whose windows are loaded before any is used
 constexpr int kMargin = 32;                // records the window starts before the interpolated position
 constexpr int kWords = kSub / 32;          // bitmap words per sub-tile: 256
-constexpr int kSubsPerGroup = 1024;         // n <= 2^31-1 gives at most 1024 groups
-constexpr int kCap = 1024;    // distinct indices of a sub-tile accumulated per round
-               // records staged in LDS per round of the emission
+constexpr int kSubsPerGroup = 1024;        // n <= 2^31-1 gives at most 1024 groups
+constexpr int kCap = 1024;                 // distinct indices of a sub-tile accumulated per round of the emission
 
 // Calls f(t, i, v) for every record (i, v) of list t with lo <= i < hi, list after list
 // (t ascending); all lanes of the wave take part, one record per lane and call.

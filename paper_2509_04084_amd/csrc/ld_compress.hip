@@ -68,10 +68,7 @@ constexpr int kGroup = kTile * kTilesPerGroup;    // 262144 elements per small-p
 constexpr int kBins = 2048;
 constexpr int kTopBin = kBins - 1;
 constexpr int kShift1 = 20, kShift2 = 9;          // radix digits: [30:20] [19:9] [8:0]
-#ifndef LD_PREP_THREADS
-#define LD_PREP_THREADS 512
-#endif
-constexpr int kPrepThreads = LD_PREP_THREADS;
+constexpr int kPrepThreads = 512;
 constexpr int kSample = 16384;                        // sampled elements per segment
 constexpr int kSampleItems = kSample / kPrepThreads;
 static_assert(kSampleItems <= 32 && kSampleItems % 8 == 0, "valid mask is 32 bits; loads go in batches of 8");
