@@ -68,6 +68,23 @@ def test_compress_ragged_segments():
     check_compress(g, r, off, (np.array(sizes) // 2).astype(np.int32), tag="k=n/2")
 
 
+def test_compress_thousands_of_small_segments():
+    # 3,000 segments (a model of many small tensors): the segment table travels in seven launches,
+    # most segments are smaller than the sample and a tile, a few span several tiles
+    rs = np.random.RandomState(11)
+    sizes = [int(x) for x in rs.randint(0, 2000, size=3000)]
+    for j in range(0, 3000, 250):
+        sizes[j] = int(rs.randint(5000, 40000))
+    off = synth.seg_offsets(sizes)
+    n = int(off[-1])
+    g = (rs.standard_t(3, n) * 1e-3).astype(np.float32)
+    r = (rs.standard_normal(n) * 1e-3).astype(np.float32)
+    k = synth.seg_topk(sizes, 1, 100) * (np.array(sizes) > 0)
+    check_compress(g, r, off, k, tag="3000 segments rho=1%")
+    k2 = np.array([int(rs.randint(0, s + 1)) for s in sizes], np.int32)
+    check_compress(g, r, off, k2, tag="3000 segments random k")
+
+
 @pytest.mark.parametrize("n", [150001])
 def test_compress_adversarial(n):
     off = np.array([0, 1000, 70000, n], np.int64)
