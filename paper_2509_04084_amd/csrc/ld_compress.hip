@@ -77,7 +77,7 @@ constexpr float kSampleZ = 6.5f;                  // safety margin of the rank e
 constexpr int kGatherBase = 4096;                 // gather list of a segment: kGatherBase + n_s / kGatherPer keys
 constexpr int kGatherPer = 4096;
 constexpr int kSegPerLaunch = 448;
-constexpr int kFullGrid = 1024;                   // workgroups of the (normally idle) k_full_* kernels
+constexpr int kFullGrid = 4096;                   // most workgroups of the (normally idle) k_full_* kernels
 constexpr uint32_t kModeCand = 0, kModeFull = 1, kModeTies = 2;
 constexpr uint32_t kTieSuspect = 512;             // sample keys equal to the candidate threshold (of 16384) that make a segment "tied"
 
