@@ -17,11 +17,19 @@ is carried from step to step, as in training: nothing is restored inside the
 timed region.  `value` is gradient bytes turned into (and merged from)
 differential checkpoints per second over the whole step.
 
+After the timed steps, outside the timed region: the outputs are verified (properties on the
+last timed step's records and snapshots, then one more step of the same buffers and launch
+configuration with the state saved before its last calls, checked against the CPU oracle on
+sampled segments, slices and layers: "verified" in the line, non-zero exit on a mismatch); the
+next rows, the small configurations and the configuration model are measured; the CPU oracle is
+timed on a bounded sample (one thread, then all cores).
+
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
 from __future__ import annotations
 
 import argparse
+import concurrent.futures
 import json
 import os
 import sys
@@ -42,6 +50,28 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, vendor figure
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def bits(t):
+    return t.view(torch.int32)
+
+
+def np_bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+class VerifyError(AssertionError):
+    pass
+
+
+def require(cond, what):
+    if not bool(cond):
+        raise VerifyError(what)
+
+
+def stats(ms_list):
+    a = np.asarray(ms_list, dtype=np.float64)
+    return {"ms": float(a.mean()), "ms_median": float(np.median(a)), "ms_min": float(a.min()), "calls_timed": int(a.size)}
 
 
 class Timer:
@@ -92,6 +122,104 @@ class SparseLeg:
         tok = tm.start("merge_sparse")
         ld.ld_merge_sparse(self.w, self.idx, self.val, self.wl.lr, self.ws_m)
         tm.stop(tok)
+
+
+    # -- verification (outside the timed region)
+    def _seg_tables(self):
+        k64 = torch.from_numpy(self.k.astype(np.int64)).to(self.dev)
+        seg_of_rec = torch.repeat_interleave(torch.arange(len(self.k), device=self.dev), k64)
+        off_t = torch.from_numpy(np.asarray(self.off, np.int64)).to(self.dev)
+        return seg_of_rec, off_t
+
+    def _check_records(self, idx, seg_of_rec, off_t, what):
+        i64 = idx.to(torch.int64)
+        require(idx.numel() == self.K, f"{what}: record count")
+        require((i64[1:] > i64[:-1]).all(), f"{what}: indices not strictly ascending")
+        require((i64 >= off_t[seg_of_rec]).all() and (i64 < off_t[seg_of_rec + 1]).all(),
+                f"{what}: a record lies outside its segment")
+        return i64
+
+    def _check_threshold(self, i64, val, seg_of_rec, what):
+        n_seg = len(self.k)
+        require((self.r[i64] == 0).all() and not torch.signbit(self.r[i64]).any(), f"{what}: selected residual is not +0")
+        min_sel = torch.full((n_seg,), float("inf"), device=self.dev).scatter_reduce(
+            0, seg_of_rec, val.abs(), reduce="amin", include_self=True)
+        seg_of_elem_max = torch.zeros(n_seg, device=self.dev)
+        for s0 in range(n_seg):  # per-segment max of what was left behind
+            lo, hi = int(self.off[s0]), int(self.off[s0 + 1])
+            if hi > lo:
+                seg_of_elem_max[s0] = self.r[lo:hi].abs().max()
+        require((seg_of_elem_max <= min_sel).all(), f"{what}: an unselected magnitude exceeds a selected one")
+
+    def verify(self):
+        """Checks the last timed step's outputs by properties, then runs one more step (same buffers,
+        same launch configuration) with the state saved before its last compress call and before its
+        merge, and checks that step against the definition and the CPU oracle. Raises VerifyError."""
+        import oracle
+        seg_of_rec, off_t = self._seg_tables()
+        # (1) the window the last timed step left behind: every diff well-formed; the last call's
+        #     threshold property against the residual as it stands
+        for t in range(self.W):
+            i64 = self._check_records(self.idx[t], seg_of_rec, off_t, f"timed step, diff {t}")
+        self._check_threshold(i64, self.val[self.W - 1], seg_of_rec, "timed step, last diff")
+        # (2) one more step with saved state
+        for t in range(self.W - 1):
+            g = self.grads[self.it % len(self.grads)]
+            ld.ld_compress_topk(g, self.r, self.off, self.k, self.idx[t], self.val[t], self.ws_c)
+            self.it += 1
+        r_before = self.r.clone()
+        g = self.grads[self.it % len(self.grads)]
+        t = self.W - 1
+        ld.ld_compress_topk(g, self.r, self.off, self.k, self.idx[t], self.val[t], self.ws_c)
+        self.it += 1
+        w_before = self.w.clone()
+        ld.ld_merge_sparse(self.w, self.idx, self.val, self.wl.lr, self.ws_m)
+        torch.cuda.synchronize()
+        idx, val = self.idx[t], self.val[t]
+        i64 = self._check_records(idx, seg_of_rec, off_t, "verification step, last diff")
+        a = r_before + g  # one fp32 add per element: the definition's accumulation
+        require(torch.equal(bits(val), bits(a[i64])), "val is not r + g bit for bit")
+        self._check_threshold(i64, val, seg_of_rec, "verification step, last diff")
+        a[i64] = 0.0
+        require(torch.equal(bits(a), bits(self.r)), "residual is not r + g with the selected positions zeroed")
+        del a
+        # the oracle on sampled segments: two small ones, one of every large shape, the last
+        n_seg = len(self.k)
+        out0 = np.concatenate([[0], np.cumsum(self.k.astype(np.int64))])
+        by_size = {}
+        for s0 in range(n_seg):
+            by_size.setdefault(int(self.off[s0 + 1] - self.off[s0]), s0)
+        sample = sorted(set(list(by_size.values())[:12]) | {n_seg - 1})
+        sample = [s0 for s0 in sample if self.off[s0 + 1] - self.off[s0] <= 12_000_000][:8]
+        for s0 in sample:
+            lo, hi = int(self.off[s0]), int(self.off[s0 + 1])
+            oi, ov, orr = oracle.topk_ef(g[lo:hi].cpu().numpy(), r_before[lo:hi].cpu().numpy(),
+                                         np.array([0, hi - lo], np.int64), self.k[s0:s0 + 1], select=True)
+            o0, o1 = int(out0[s0]), int(out0[s0 + 1])
+            require(np.array_equal(idx[o0:o1].cpu().numpy(), oi + lo), f"oracle: idx of segment {s0}")
+            require(np.array_equal(np_bits(val[o0:o1].cpu().numpy()), np_bits(ov)), f"oracle: val of segment {s0}")
+            require(np.array_equal(np_bits(self.r[lo:hi].cpu().numpy()), np_bits(orr)), f"oracle: residual of segment {s0}")
+        del r_before
+        # the merge: the per-record definition redone with torch on the whole array, the oracle on slices
+        n = self.n
+        m_len = min(n, 2_000_000)
+        slices = [(0, m_len), (max(0, n // 2 - m_len // 2), max(0, n // 2 - m_len // 2) + m_len), (n - m_len, n)]
+        for (a0, b0) in slices:
+            sub_i, sub_v = [], []
+            for i_t, v_t in zip(self.idx, self.val):
+                p0 = int(torch.searchsorted(i_t.to(torch.int64), torch.tensor([a0], dtype=torch.int64, device=self.dev)))
+                p1 = int(torch.searchsorted(i_t.to(torch.int64), torch.tensor([b0], dtype=torch.int64, device=self.dev)))
+                sub_i.append((i_t[p0:p1].cpu().numpy().astype(np.int64) - a0).astype(np.int32))
+                sub_v.append(v_t[p0:p1].cpu().numpy())
+            ref = oracle.merge_sparse(w_before[a0:b0].cpu().numpy(), sub_i, sub_v, self.wl.lr)
+            require(np.array_equal(np_bits(self.w[a0:b0].cpu().numpy()), np_bits(ref)), f"oracle: merged w[{a0}:{b0}]")
+        lr_t = torch.tensor(self.wl.lr, dtype=torch.float32, device=self.dev)
+        for i_t, v_t in zip(self.idx, self.val):
+            j = i_t.to(torch.int64)
+            w_before[j] = w_before[j] - lr_t * v_t   # rounded product, then rounded difference
+            del j
+        require(torch.equal(bits(self.w), bits(w_before)), "merged w differs from the per-record definition")
+        return {"sampled_segments": [int(x) for x in sample], "merge_slices": slices}
 
     # algorithmic bytes per call
     def bytes_compress(self):
@@ -211,6 +339,38 @@ class DenseLeg:
         tm.stop(tok)
         self.step0 += self.W
 
+
+    # -- verification (outside the timed region)
+    def verify(self):
+        """The last timed step's snapshots against their sources, bit for bit; then one more step with
+        slices of (w, m, v) saved first, checked against the CPU oracle within the Adam tolerance."""
+        import oracle
+        for t in range(self.W):
+            src = self.src[(self.it - self.W + t) % len(self.src)]
+            require(torch.equal(src.view(torch.int16), self.snap[t].view(torch.int16)), f"snapshot {t} differs from its source")
+        nt = len(self.layers)
+        checked = sorted({0, 1, 5, 7, 8, nt - 2, nt - 1})
+        saved = []
+        for s0 in checked:
+            lo, hi = self.layers[s0]
+            hi = min(hi, lo + 2_000_000)
+            saved.append((lo, hi, self.w[lo:hi].cpu().numpy(), self.m[lo:hi].cpu().numpy(), self.v[lo:hi].cpu().numpy()))
+        step0 = self.step0
+        self.step(Timer())
+        torch.cuda.synchronize()
+        for t in range(self.W):
+            src = self.src[(self.it - self.W + t) % len(self.src)]
+            require(torch.equal(src.view(torch.int16), self.snap[t].view(torch.int16)), f"snapshot {t} differs from its source")
+        for lo, hi, w0, m0, v0 in saved:
+            gs = [sn[lo:hi].view(torch.int16).cpu().numpy().view(np.uint16) for sn in self.snap]
+            wr, mr, vr = oracle.adam_replay(w0, m0, v0, gs, step0, self.wl.lr, **synth.ADAM)
+            for name, got, ref in (("w", self.w, wr), ("m", self.m, mr), ("v", self.v, vr)):
+                x = got[lo:hi].cpu().numpy().astype(np.float64)
+                require(np.all(np.abs(x - ref) <= 1e-7 + 1e-6 * np.abs(ref)), f"oracle: Adam {name}[{lo}:{hi}]")
+            xv = self.v[lo:hi].cpu().numpy().astype(np.float64)
+            require(np.all(np.abs(xv - vr) <= 2e-6 * np.abs(vr)), f"oracle: Adam v[{lo}:{hi}], relative")
+        return {"sampled_layers": [int(x) for x in checked], "adam_step0": int(step0)}
+
     # -- next row: the paper's snapshot destination, pinned host memory (bound by the host link, not HBM)
     def time_snapshot_to_host(self, reps=3):
         lo, hi = self.layers[-1]  # the head: 131 M elements, 262 MB
@@ -263,62 +423,226 @@ def measured_traffic(path):
     return out
 
 
-def cpu_baseline():
-    """The CPU oracle, as it stands (single thread), on a bounded sample of the same workload:
-    about 10-20 s of host work, extrapolated to the full step by gradient bytes."""
+def host_cores():
+    """(threads the all-core leg uses, logical CPUs this process may run on, CPU model string)."""
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return max(1, min(avail, 16)), avail, model  # a one-GPU box's CPU share is 16 threads whatever nproc says
+
+
+def cpu_baseline(gen_dev="cpu"):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload (about 20 s of host
+    work), extrapolated to the full step by gradient bytes: once on one thread, once on all cores
+    (threads of this harness over independent segments / parameter ranges; the oracle itself stays
+    single-threaded and untouched). The inputs are drawn on `gen_dev` (the GPU when there is one:
+    drawing 2.5 G Student-t values is what would take minutes on the host) and handed over as host arrays."""
     import oracle
+    threads, avail, model = host_cores()
     xl, ll = synth.workload("gpt2xl"), synth.workload("llama7b")
-    # sparse: the four weight matrices of two transformer blocks (61 M elements), 10 chained diffs
-    segs = [4, 6, 10, 12, 16, 18, 22, 24]
-    sizes = [xl.sizes[s] for s in segs]
-    off, k = synth.seg_offsets(sizes), synth.seg_topk(sizes, *xl.rho)
-    n = int(off[-1])
-    Wc = 10
-    grads = []
-    for t in range(Wc):
-        g = np.empty(n, np.float32)
-        for j, s in enumerate(segs):
-            g[off[j]:off[j + 1]] = synth.gradient_segment(xl, t, s, "cpu").numpy()
-        grads.append(g)
-    w0 = synth.base_weights(n).numpy()
-    t0 = time.perf_counter()
-    r = np.zeros(n, np.float32)
-    idxs, vals = [], []
-    for g in grads:
-        i, v, r = oracle.topk_ef(g, r, off, k, select=True)
-        idxs.append(i)
-        vals.append(v)
-    oracle.merge_sparse(w0, idxs, vals, xl.lr)
-    t_sparse = time.perf_counter() - t0
-    sparse_bytes = 4 * n * Wc
-    del grads
-    # dense: the seven weight matrices of the first block (202 M elements), W = 4
-    dsegs = [1, 2, 3, 4, 5, 6, 7]
-    Wd = ll.window
-    t_dense, nd = 0.0, 0
-    for s in dsegs:
-        ns = ll.sizes[s]
-        gs = [synth.gradient_layer_bf16(ll, t, s, "cpu").view(torch.int16).numpy().view(np.uint16) for t in range(Wd)]
-        wd = synth.base_weights(ns).numpy()
-        z = np.zeros(ns, np.float32)
-        t0 = time.perf_counter()
+    Wc, Wd = 10, ll.window
+
+    def sparse_inputs(segs):
+        out = []
+        for s in segs:
+            ns = xl.sizes[s]
+            gs = [synth.gradient_segment(xl, t, s, gen_dev).cpu().numpy() for t in range(Wc)]
+            out.append((ns, gs, synth.base_weights(ns, gen_dev).cpu().numpy()))
+        return out
+
+    def sparse_chain(item):  # one segment: Wc chained top-k calls and the merge of its window
+        ns, gs, w0 = item
+        off, k = np.array([0, ns], np.int64), synth.seg_topk([ns], *xl.rho)
+        r = np.zeros(ns, np.float32)
+        idxs, vals = [], []
+        for g in gs:
+            i, v, r = oracle.topk_ef(g, r, off, k, select=True)
+            idxs.append(i)
+            vals.append(v)
+        oracle.merge_sparse(w0, idxs, vals, xl.lr)
+
+    def dense_inputs(layers, parts):
+        out = []
+        for s in layers:
+            ns = ll.sizes[s]
+            gs = [synth.gradient_layer_bf16(ll, t, s, gen_dev).view(torch.int16).cpu().numpy().view(np.uint16)
+                  for t in range(Wd)]
+            wd = synth.base_weights(ns, gen_dev).cpu().numpy()
+            cut = np.linspace(0, ns, parts + 1).astype(np.int64)
+            for a0, b0 in zip(cut[:-1], cut[1:]):
+                out.append((wd[a0:b0], [g[a0:b0] for g in gs]))
+        return out
+
+    def dense_range(item):  # one parameter range: W snapshots and the Adam replay over them
+        wd, gs = item
+        z = np.zeros(wd.size, np.float32)
         snaps = [oracle.snapshot(g) for g in gs]
         oracle.adam_replay(wd, z, z, snaps, 0, ll.lr, **synth.ADAM)
-        t_dense += time.perf_counter() - t0
-        nd += ns
-    dense_bytes = 2 * nd * Wd
-    # weight the two legs as the full step does (gradient bytes of each leg)
+
+    def timed(fn, items, nthreads):
+        t0 = time.perf_counter()
+        if nthreads == 1:
+            for it in items:
+                fn(it)
+        else:  # ctypes releases the interpreter lock while the oracle runs
+            with concurrent.futures.ThreadPoolExecutor(nthreads) as ex:
+                list(ex.map(fn, items))
+        return time.perf_counter() - t0
+
     full_sparse = 4 * xl.n * xl.window
     full_dense = 2 * ll.n * ll.window
-    est_full_s = t_sparse * full_sparse / sparse_bytes + t_dense * full_dense / dense_bytes
-    value = (full_sparse + full_dense) / est_full_s / 1e9
+
+    def extrapolate(t_sparse, n_sparse, t_dense, n_dense):
+        sb, db = 4 * n_sparse * Wc, 2 * n_dense * Wd
+        est = t_sparse * full_sparse / sb + t_dense * full_dense / db
+        return (full_sparse + full_dense) / est / 1e9, sb / t_sparse / 1e9, db / t_dense / 1e9
+
+    # one thread: the four weight matrices of two transformer blocks (61 M elements), the seven
+    # weight matrices of the first llama block (202 M elements)
+    segs1 = [4, 6, 10, 12, 16, 18, 22, 24]
+    lay1 = [1, 2, 3, 4, 5, 6, 7]
+    it_s, it_d = sparse_inputs(segs1), dense_inputs(lay1, 1)
+    n_s1, n_d1 = sum(x[0] for x in it_s), sum(x[0].size for x in it_d)
+    t_s1, t_d1 = timed(sparse_chain, it_s, 1), timed(dense_range, it_d, 1)
+    v1, s1, d1 = extrapolate(t_s1, n_s1, t_d1, n_d1)
+    log(f"[cpu_baseline] 1 thread: sparse {t_s1:.2f} s, dense {t_d1:.2f} s")
+    # all cores: the weight matrices of eight blocks (one chain per matrix), the same llama layers cut
+    # into ranges
+    segsN = [4 + 12 * b + j for b in range(8) for j in (0, 2, 6, 8)]
+    it_sN = sparse_inputs(segsN)
+    it_dN = dense_inputs(lay1, max(1, threads // 2))
+    n_sN, n_dN = sum(x[0] for x in it_sN), sum(x[0].size for x in it_dN)
+    del it_s, it_d
+    t_sN, t_dN = timed(sparse_chain, it_sN, threads), timed(dense_range, it_dN, threads)
+    vN, sN, dN = extrapolate(t_sN, n_sN, t_dN, n_dN)
+    log(f"[cpu_baseline] {threads} threads: sparse {t_sN:.2f} s, dense {t_dN:.2f} s")
     return {
-        "value": value, "unit": "GB/s (gradient bytes)", "cores": 1, "kind": "oracle",
-        "sample": (f"gpt2xl segments {segs} ({n:,} elements), {Wc} chained top-k (nth_element variant) + "
-                   f"window merge: {t_sparse:.2f} s; llama7b layers {dsegs} ({nd:,} elements), snapshot + Adam "
-                   f"replay W={Wd}: {t_dense:.2f} s; extrapolated to the full step by gradient bytes"),
-        "sparse_GBps": sparse_bytes / t_sparse / 1e9, "dense_GBps": dense_bytes / t_dense / 1e9,
+        "value": vN, "unit": "GB/s (gradient bytes)", "cores": threads, "kind": "oracle",
+        "sample": (f"all-core leg ({threads} threads of the harness over independent work items): gpt2xl segments "
+                   f"{segsN[0]}..{segsN[-1]} (32 weight matrices, {n_sN:,} elements), {Wc} chained top-k (nth_element variant) "
+                   f"+ window merge per matrix: {t_sN:.2f} s; llama7b layers {lay1} ({n_dN:,} elements) in "
+                   f"{len(it_dN)} ranges, snapshot + Adam replay W={Wd}: {t_dN:.2f} s; extrapolated to the full step by "
+                   f"gradient bytes"),
+        "sparse_GBps": sN, "dense_GBps": dN,
+        "single_thread": {
+            "value": v1, "cores": 1, "sparse_GBps": s1, "dense_GBps": d1, "sparse_s": t_s1, "dense_s": t_d1,
+            "sample": (f"gpt2xl segments {segs1} ({n_s1:,} elements), {Wc} chained top-k + window merge; llama7b layers "
+                       f"{lay1} ({n_d1:,} elements), snapshot + Adam replay W={Wd}")},
+        "all_cores": {"sparse_s": t_sN, "dense_s": t_dN},
+        "nproc": avail, "cpu_model": model,
     }
+
+
+def config_model_row(sparse):
+    """Sec. V-C closed loop: the costs of Eqs. (8) and (9) measured with this library on the sparse
+    leg's window, fed to ld_config_select over the 24 candidates of the paper's Example
+    (f in {10, 30, 50, 100}, b in {1..6}).
+      C_replay(b)  ld_merge_sparse of b diffs resident in HBM (HIP events)
+      R_B(b)       ld_merge_sparse_from_host of b diffs: read over the host link + replay (wall clock);
+                   decompression is part of the merge kernels
+      C_B(b)       the b diffs copied device -> page-locked host memory, persistence's first hop
+                   (storage is out of scope here), wall clock
+      C_F, R_F     a full checkpoint (w, m, v: 12 n bytes) over the host link, from one measured copy of w each way
+    N, T, M and tau are stated, not measured: nothing here trains."""
+    dev = sparse.dev
+    fs, bs = (10, 30, 50, 100), (1, 2, 3, 4, 5, 6)
+    nb = max(bs)
+    hi = [torch.empty(t.shape, dtype=t.dtype, pin_memory=True).copy_(t) for t in sparse.idx[:nb]]
+    hv = [torch.empty(t.shape, dtype=t.dtype, pin_memory=True).copy_(t) for t in sparse.val[:nb]]
+    oi = [torch.empty(t.shape, dtype=t.dtype, pin_memory=True) for t in sparse.idx[:nb]]
+    ov = [torch.empty(t.shape, dtype=t.dtype, pin_memory=True) for t in sparse.val[:nb]]
+    K = [t.numel() for t in sparse.idx[:nb]]
+    lib = ld.load()
+    Kh = np.asarray(K, np.int64)
+    staging = torch.empty(int(lib.ld_merge_sparse_from_host_staging(Kh.ctypes.data, nb, nb)), dtype=torch.uint8, device=dev)
+    ws = torch.empty(ld.ld_merge_sparse_workspace(sparse.n, K), dtype=torch.uint8, device=dev)
+    st = torch.cuda.current_stream()
+
+    def wall(fn, reps=3):
+        best = []
+        for _ in range(reps + 1):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            best.append(time.perf_counter() - t0)
+        return float(np.median(best[1:]))
+
+    c_replay, r_b, c_b = {}, {}, {}
+    for b in bs:
+        tm = Timer()
+        for _ in range(4):
+            tok = tm.start("m")
+            ld.ld_merge_sparse(sparse.w, sparse.idx[:b], sparse.val[:b], sparse.wl.lr, ws)
+            tm.stop(tok)
+        torch.cuda.synchronize()
+        c_replay[b] = float(np.median(tm.ms()["m"][1:])) * 1e-3
+        r_b[b] = wall(lambda: ld.ld_merge_sparse_from_host(sparse.w, hi[:b], hv[:b], sparse.wl.lr, group=b, staging=staging,
+                                                           workspace=ws, copy_stream=st, merge_stream=st))
+
+        def persist():
+            for t in range(b):
+                oi[t].copy_(sparse.idx[t], non_blocking=True)
+                ov[t].copy_(sparse.val[t], non_blocking=True)
+        c_b[b] = wall(persist)
+    hw = torch.empty(sparse.n, dtype=torch.float32, pin_memory=True)
+    c_f = 3.0 * wall(lambda: hw.copy_(sparse.w, non_blocking=True), reps=2)
+    r_f = 3.0 * wall(lambda: sparse.w.copy_(hw, non_blocking=True), reps=2)  # the same bits back: w is unchanged
+    del hw
+    P = dict(N=1.0, T=86400.0, M=3600.0, tau=1.0, R_F=r_f, C_F=c_f)
+    cf, cb = [f for f in fs for _ in bs], [b for _ in fs for b in bs]
+    best, tw = ld.ld_config_select(ld.ConfigParams(**P), cf, cb, [r_b[b] for b in cb], [c_b[b] for b in cb])
+    grid = {f"f={f}": [float(tw[i * len(bs) + j] / tw[best]) for j in range(len(bs))] for i, f in enumerate(fs)}
+    return {
+        "selected": {"f": int(cf[best]), "b": int(cb[best]), "T_w_s": float(tw[best])},
+        "T_w_normalised": grid, "b_values": list(bs),
+        "f_c": {str(b): ld.ld_config_critical_interval(ld.ConfigParams(**P), b, r_b[b], c_b[b]) for b in bs},
+        "measured_s": {"C_replay": {str(b): c_replay[b] for b in bs}, "R_B": {str(b): r_b[b] for b in bs},
+                       "C_B": {str(b): c_b[b] for b in bs}, "C_F": c_f, "R_F": r_f},
+        "stated": {"N": P["N"], "T_s": P["T"], "M_s": P["M"], "tau_s": P["tau"]},
+        "note": "Eqs. (8)-(12) of Sec. V-C through ld_config_select; R_B(b) = read of b diffs from page-locked host memory "
+                "+ replay (ld_merge_sparse_from_host), C_B(b) = the b diffs copied to page-locked host memory, C_F / R_F = "
+                "12 n bytes over the host link; N, T, M, tau stated (no training runs here); not part of `value`"}
+
+
+def small_configs(dev, steps=3):
+    """Configurations 1-3 (the parity-test cases): compress and window-merge time per call, and the
+    same verification as the main legs. Their whole traffic fits the last-level cache or is a few
+    launches long: latencies, not roofline fractions, and not part of `value`."""
+    out = {}
+    for name in ("flat1m", "resnet50", "gpt2s"):
+        wl = synth.workload(name)
+        leg = SparseLeg(wl, dev, pool=min(10, wl.window))
+        leg.step(Timer())
+        tm = Timer()
+        torch.cuda.synchronize()
+        for _ in range(steps):
+            leg.step(tm)
+        torch.cuda.synchronize()
+        ms = tm.ms()
+        leg.verify()
+        c, m = stats(ms["compress"]), stats(ms["merge_sparse"])
+        out[name] = {
+            "n": leg.n, "segments": len(wl.sizes), "K": leg.K, "W": leg.W,
+            "compress_us": {"mean": 1e3 * c["ms"], "median": 1e3 * c["ms_median"], "min": 1e3 * c["ms_min"]},
+            "merge_window_us": {"mean": 1e3 * m["ms"], "median": 1e3 * m["ms_median"], "min": 1e3 * m["ms_min"]},
+            "compress_algorithmic_GBps": leg.bytes_compress() / (c["ms_median"] * 1e-3) / 1e9,
+            "merge_algorithmic_GBps": leg.bytes_merge() / (m["ms_median"] * 1e-3) / 1e9,
+            "verified": True,
+            "bound": "launch latency / last-level cache" if name != "gpt2s" else "partly HBM (0.5 GB per array), partly launch latency"}
+        log(f"[small] {name}: compress {1e3 * c['ms_median']:.0f} us, window merge {1e3 * m['ms_median']:.0f} us (medians), verified")
+        del leg
+    return out
 
 
 def main():
@@ -333,6 +657,8 @@ def main():
                     help="comma list of sparse, dense, copycal (copycal: a 1 GiB plain copy, for counter calibration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true", help="skip the calls measured outside the step")
+    ap.add_argument("--no-verify", action="store_true", help="skip the check of the outputs (profiling runs)")
+    ap.add_argument("--no-small-configs", action="store_true", help="skip the three small configurations")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
@@ -369,15 +695,37 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    per = {k: float(np.mean(v)) for k, v in tm.ms().items()}
+    all_ms = tm.ms()
+    per = {k: float(np.mean(v)) for k, v in all_ms.items()}
     log(f"[timed] {args.steps} steps, {ms_per_step:.2f} ms/step; mean ms per call: {per}")
+
+    # the outputs of what was just timed, checked outside the timed region
+    verified = None
+    if not args.no_verify:
+        verified = {}
+        try:
+            if sparse:
+                t1 = time.perf_counter()
+                verified["sparse"] = sparse.verify()
+                log(f"[verify] sparse leg ok ({time.perf_counter() - t1:.1f} s)")
+            if dense:
+                t1 = time.perf_counter()
+                verified["dense"] = dense.verify()
+                log(f"[verify] dense leg ok ({time.perf_counter() - t1:.1f} s)")
+        except VerifyError as e:
+            log(f"[verify] FAILED: {e}")
+            print(json.dumps({"verified": False, "error": str(e)}), flush=True)
+            sys.exit(3)
 
     grad_bytes = (sparse.grad_bytes() if sparse else 0) + (dense.grad_bytes() if dense else 0)
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
 
     def roof(name, nbytes):
         ach = nbytes / (per[name] * 1e-3) / 1e9
-        return {"ms": per[name], "algorithmic_bytes": nbytes, "achieved_GBps": ach, "frac": ach / HBM_PEAK_GBS}
+        out = stats(all_ms[name])
+        out.update({"algorithmic_bytes": nbytes, "achieved_GBps": ach, "frac": ach / HBM_PEAK_GBS,
+                    "frac_at_median": nbytes / (out["ms_median"] * 1e-3) / 1e9 / HBM_PEAK_GBS})
+        return out
 
     calls = {}
     if sparse:
@@ -427,6 +775,10 @@ def main():
             "host_link_GBps": nb / (rec["pipelined"] * 1e-3) / 1e9,
             "note": "the window's 20 diffs in page-locked host memory, copied in groups of 5 on one stream while "
                     "the previous group is merged on another; wall-clock; bound by the host link; not part of `value`"}
+    if sparse and not args.no_next_rows:
+        next_rows["config_model"] = config_model_row(sparse)
+        sel = next_rows["config_model"]["selected"]
+        log(f"[next row] configuration model: selected (f, b) = ({sel['f']}, {sel['b']})")
     if dense and not args.no_next_rows:
         ms, nb = dense.time_snapshot_to_host()
         log(f"[next row] ld_snapshot_layer into pinned host memory: {ms:.2f} ms for {nb / 1e6:.0f} MB")
@@ -446,9 +798,10 @@ def main():
         c["traffic_bytes"] = traffic.get(name.split("(")[0])
     roofline = {"bound": "hbm", "kernel": dom, "achieved": calls[dom]["achieved_GBps"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": calls[dom]["frac"], "traffic": calls[dom]["traffic_bytes"],
-                "note": "per call of the entry point (all its kernels), HIP events on the launch stream; "
-                        "traffic = HBM bytes per call from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by "
-                        "what the same counter reads for a 1 GiB plain copy (profiles/)"}
+                "note": "achieved: per call of the entry point (all its kernels), mean over the timed calls, HIP events on "
+                        "the launch stream, measured in this run; traffic: NOT measured in this run - HBM bytes per "
+                        "call from the committed counter summary profiles/hbm_traffic_gpt2xl_llama7b.txt (rocprofv3 "
+                        "FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB plain copy)"}
     if dense:
         # the layer snapshots are plain copies: what a copy kernel reaches on this machine in this run
         roofline["plain_copy_GBps"] = calls["ld_snapshot_layers(x34)"]["achieved_GBps"]
@@ -466,11 +819,23 @@ def main():
                              f"snapshots per model layer ({len(dense.groups)} calls) + fused Adam replay") if dense else None},
         "roofline": roofline, "calls": calls,
     }
+    if verified is not None:
+        out["verified"] = True
+        out["verification"] = verified
     if next_rows:
         out["next_rows"] = next_rows
+    del sparse, dense, copycal
+    torch.cuda.empty_cache()
+    if not args.no_small_configs:
+        try:
+            out["small_configs"] = small_configs(dev)
+        except VerifyError as e:
+            log(f"[verify] FAILED on a small configuration: {e}")
+            print(json.dumps({"verified": False, "error": str(e)}), flush=True)
+            sys.exit(3)
     if not args.no_cpu_baseline:
         log("[cpu_baseline] timing the oracle on a bounded sample ...")
-        out["cpu_baseline"] = cpu_baseline()
+        out["cpu_baseline"] = cpu_baseline(gen_dev=str(dev))
     print(json.dumps(out), flush=True)
 
 

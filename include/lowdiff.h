@@ -129,6 +129,33 @@ ld_status ld_compress_topk_strategy(const float* grad, float* residual,
                                     void* workspace, size_t workspace_bytes, ld_stream stream,
                                     int32_t strategy);
 
+/* Which way the last ld_compress_topk call on `workspace` went, segment by segment (a test and
+ * diagnosis hook: the result of a call never depends on it).  Enqueues one small kernel on
+ * `stream`, after which
+ *   paths[s] & 0xFF     LD_PATH_CANDIDATES: the top-k was resolved among the sampled-threshold
+ *                       candidates; LD_PATH_TIES: same, the threshold being a massively repeated
+ *                       key whose ties were taken in index order; LD_PATH_FULL: the segment was
+ *                       redone by the radix select over all its elements
+ *   paths[s] & 0x100    the sample of the segment held one key so often that the candidates were
+ *                       taken above it
+ *   paths[s] & 0x10000  the full-segment pass gave up waiting at its grid barrier (its workgroups
+ *                       were never all resident: more compress calls in flight on one GPU than
+ *                       it holds); the outputs of that call are not valid
+ *   overflowed_tiles[s] 4096-element tiles of the segment with more candidates than a slot holds
+ *                       (they were read back from the residual); may be NULL
+ *
+ *   workspace  dev, the workspace of that call, unchanged since
+ *   n_seg, seg_off      the segment table of that call (host)
+ *   paths, overflowed_tiles  dev [n_seg] int32
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_WORKSPACE, LD_ERR_HIP.
+ */
+#define LD_PATH_CANDIDATES 0
+#define LD_PATH_FULL       1
+#define LD_PATH_TIES       2
+ld_status ld_compress_topk_paths(const void* workspace, size_t workspace_bytes, int32_t n_seg,
+                                 const int64_t* seg_off /* host */, int32_t* paths,
+                                 int32_t* overflowed_tiles, ld_stream stream);
+
 /* ------------------------------------------------------------------------
  * ld_snapshot_layer - bit-exact copy of one layer's bf16 gradient into a
  * checkpoint-owned buffer, so training may overwrite its gradient buffer.

@@ -63,6 +63,7 @@ extern "C" ld_status ld_check_diff(const int32_t* idx, const float* val, int64_t
     const int64_t blocks = (K + kCheckThreads * kCheckPer - 1) / (kCheckThreads * kCheckPer);
     if (blocks > INT32_MAX) return LD_ERR_RANGE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    ld_begin_call();
     unsigned long long* out = reinterpret_cast<unsigned long long*>(counts);
     k_check_zero<<<dim3(1), dim3(LD_WAVE), 0, s>>>(out);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;

@@ -298,6 +298,7 @@ extern "C" ld_status ld_combine_sparse(const int32_t* const* idx, const float* c
     if (out_cap > 0 && (!out_idx || !out_val)) return LD_ERR_NULL;
     if (!ld_aligned(out_idx, 4) || !ld_aligned(out_val, 4)) return LD_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    ld_begin_call();
     const int32_t nsub = static_cast<int32_t>((n + kSub - 1) / kSub);
     const int32_t ngrp = (nsub + kSubsPerGroup - 1) / kSubsPerGroup;
     if (n == 0 || N == 0 || total == 0) {  // an empty result: only the count is written
@@ -325,8 +326,11 @@ extern "C" ld_status ld_combine_sparse(const int32_t* const* idx, const float* c
     launch_chunks(tb, N, n, nchunk, ctab, s);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     k_combine_count<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts);
+    if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     k_combine_groups<<<dim3(ngrp), dim3(256), 0, s>>>(counts, nsub, gsum);
+    if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     k_combine_scan<<<dim3(1), dim3(1024), 0, s>>>(gsum, goff, ngrp, out_count);
+    if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     k_combine_emit<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts, nsub, gsum, goff, scale, out_idx, out_val,
                                          out_cap);
     return ld_launch_status();

@@ -9,7 +9,14 @@
 
 #define LD_WAVE 64
 
-// Status of the launches enqueued since the last check (reading it also clears the error).
+// An entry point calls this once, after its argument checks and before its first launch: an
+// error that the caller's own earlier HIP calls left behind in this thread is dropped here, so
+// that it is not taken for a failure of this call's launches.
+static inline void ld_begin_call() { (void)hipGetLastError(); }
+
+// Status of the launch just enqueued (reading it also clears the error). Checked after every
+// launch: when it is not LD_OK the entry point returns at once, with earlier kernels of the
+// call already enqueued - the outputs are then unspecified.
 static inline ld_status ld_launch_status() {
     return hipGetLastError() == hipSuccess ? LD_OK : LD_ERR_HIP;
 }

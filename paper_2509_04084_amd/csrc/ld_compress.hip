@@ -8,8 +8,11 @@
 // Design: ONE streaming pass over gradient and residual, then three small passes
 // over a candidate set of about 1.7 * k elements.
 //
-//   k_upload  segment tables (kernel arguments -> workspace).
-//   k_prep    one workgroup per segment: from a 16K-element sample of |r+g| it
+//   k_prep    one workgroup per segment. The segment table travels in its kernel arguments,
+//             packed as a dictionary of the distinct (length, k) pairs plus one byte per
+//             segment (a model has few distinct tensor shapes); every workgroup rebuilds the
+//             prefix sums it needs from it. Tables that do not pack (more than 160 distinct
+//             pairs or 2048 segments) go through k_upload launches first. From a 16K-element sample of |r+g| it
 //             estimates three keys: a candidate threshold tau (the sample key at a
 //             rank high enough that, with overwhelming probability, at least k
 //             elements of the segment lie at or above it), the likeliest threshold
@@ -50,9 +53,12 @@
 // passes (16, 32 or 64) are chosen per call from the densities seg_k / n_s, so that calls
 // at 5 or 10 % keep the same structure (the paper varies rho from 0.001 to 0.1, Exp. 10).
 // Per-segment steps run as kernels of their own (a kernel boundary is the only
-// device-wide hand-over the normal path needs); the k_full_* kernels hand over
-// with a ticket counter (device-scope release / acquire).
+// device-wide hand-over the normal path needs). The full-segment path is ONE launch (k_full)
+// that returns at once when no segment was handed to it; otherwise its five phases hand over
+// through a barrier across the grid, which is kept small enough to be resident as a whole.
 #include <math.h>
+
+#include <atomic>
 
 #include "ld_common.h"
 
@@ -77,11 +83,14 @@ constexpr float kSampleZ = 6.5f;                  // safety margin of the rank e
 constexpr int kGatherBase = 4096;                 // gather list of a segment: kGatherBase + n_s / kGatherPer keys
 constexpr int kGatherPer = 4096;
 constexpr int kSegPerLaunch = 448;
-constexpr int kFullGrid = 4096;                   // most workgroups of the (normally idle) k_full_* kernels
+constexpr int kFullGrid = 1024;                   // most workgroups of the (normally idle) k_full kernel
 constexpr uint32_t kModeCand = 0, kModeFull = 1, kModeTies = 2;
 constexpr uint32_t kTieSuspect = 512;             // sample keys equal to the candidate threshold (of 16384) that make a segment "tied"
 
 constexpr uint32_t kOverflow = 0xFFFFFFFFu;       // tile count: slot too small, read the residual
+constexpr int kSyncCount = 0, kSyncArrived = 1, kSyncGaveUp = 2, kSyncWords = 3;
+constexpr int kDictMax = 160;                     // distinct (length, k) pairs of a packed segment table
+constexpr int kDictSegs = 2048;                   // segments of a packed segment table
 
 struct SegDesc {        // one per segment plus a sentinel
     int64_t off;        // first element
@@ -139,7 +148,7 @@ struct Ctx {
     uint32_t* gkey;         // [n_seg][kGatherCap]
     int32_t* gtile;         // [n_seg][kGatherCap]
     int32_t* fail_groups;   // [n_group] groups of segments in kModeFull
-    uint32_t* fail_count;   // [1]
+    uint32_t* fail_count;   // [kSyncWords]: groups listed; arrivals at k_full's grid barrier; its give-up flag
     int32_t n_seg;
     int32_t n_group;
     int32_t slot;           // candidates a tile can store (kSlotMin .. kSlotMax, multiple of 64)
@@ -154,6 +163,19 @@ struct UploadBatch {
     int32_t count;
     int32_t n_seg;
 };
+
+// The segment table as k_prep takes it in its arguments when it packs: n_seg = 0 says that it
+// did not and that k_upload has written the descriptors.
+struct PackedTable {
+    uint32_t len[kDictMax];
+    uint32_t k[kDictMax];
+    uint32_t off0[kDictSegs / LD_WAVE];    // per bucket of 64 segments: elements,
+    uint32_t out0[kDictSegs / LD_WAVE];    //   records
+    uint32_t group0[kDictSegs / LD_WAVE];  //   and groups before it
+    uint8_t code[kDictSegs];
+    int32_t n_seg;
+};
+static_assert(sizeof(PackedTable) + sizeof(Ctx) + 24 <= 4096, "k_prep's arguments must fit a kernel's 4 KB");
 
 __host__ __device__ inline int64_t align_down4(int64_t x) { return x & ~static_cast<int64_t>(3); }
 
@@ -369,18 +391,58 @@ __global__ __launch_bounds__(512) void k_upload(UploadBatch ub, Ctx c) {
     if (s == ub.n_seg - 1)
         c.desc[s + 1] = SegDesc{ub.off[j + 1], ub.out0 + ks + my_k, 0,
                                 ub.group0 + static_cast<int32_t>(groups + my_groups)};
-    if (s == 0) *c.fail_count = 0;
+    if (s == 0)
+        for (int i = 0; i < kSyncWords; ++i) c.fail_count[i] = 0;
+}
+
+// Descriptor of segment `s` and the end of its range from the packed table. The host has summed
+// the segments of every bucket of 64; what is left is a prefix over the segments of the own
+// bucket before `s`: one lane per segment, three scans across the first wave.
+__device__ __forceinline__ SegDesc desc_from_table(const PackedTable& pt, int32_t s, int64_t& end) {
+    __shared__ uint32_t found[5];
+    if (threadIdx.x < LD_WAVE) {
+        const int bucket = s / LD_WAVE, lane = threadIdx.x;
+        const int j = bucket * LD_WAVE + lane;
+        const bool live = j < pt.n_seg;
+        const uint32_t code = live ? pt.code[j] : 0u;
+        const uint32_t len = live ? pt.len[code] : 0u, kk = live ? pt.k[code] : 0u;
+        const uint32_t off = pt.off0[bucket] + ld_wave_iscan(len) - len;   // n <= 2^31 - 1: the sums fit 32 bits
+        const uint32_t out0 = pt.out0[bucket] + ld_wave_iscan(kk) - kk;
+        const uint32_t groups = static_cast<uint32_t>(groups_of(off, static_cast<int64_t>(off) + len));
+        const uint32_t group0 = pt.group0[bucket] + ld_wave_iscan(groups) - groups;
+        if (j == s) {
+            found[0] = off; found[1] = len; found[2] = out0; found[3] = kk; found[4] = group0;
+        }
+    }
+    __syncthreads();
+    end = static_cast<int64_t>(found[0]) + found[1];
+    return SegDesc{static_cast<int64_t>(found[0]), static_cast<int64_t>(found[2]), static_cast<int32_t>(found[3]),
+                   static_cast<int32_t>(found[4])};
 }
 
 __global__ __launch_bounds__(kPrepThreads) void k_prep(const float* __restrict__ g,
                                                        const float* __restrict__ r, Ctx c,
-                                                       int32_t no_estimate) {
+                                                       int32_t no_estimate, PackedTable pt) {
     __shared__ uint32_t lh[3 * kBins];
     __shared__ uint32_t sh[kPrepThreads / LD_WAVE];
     __shared__ uint32_t res[6];
     const int s = blockIdx.x;
-    const SegDesc d = c.desc[s];
-    const int64_t off = d.off, end = c.desc[s + 1].off;
+    SegDesc d;
+    int64_t end;
+    if (pt.n_seg > 0) {
+        d = desc_from_table(pt, s, end);
+        if (threadIdx.x == 0) {
+            c.desc[s] = d;
+            if (s == pt.n_seg - 1)
+                c.desc[s + 1] = SegDesc{end, d.out0 + d.k, 0, d.group0 + groups_of(d.off, end)};
+            if (s == 0)
+                for (int i = 0; i < kSyncWords; ++i) c.fail_count[i] = 0;
+        }
+    } else {
+        d = c.desc[s];
+        end = c.desc[s + 1].off;
+    }
+    const int64_t off = d.off;
     const int32_t k = d.k;
     const int32_t ngroup = groups_of(off, end);
     if (threadIdx.x < sizeof(SegState) / 4) reinterpret_cast<uint32_t*>(&c.state[s])[threadIdx.x] = 0;
@@ -691,29 +753,75 @@ struct Trip {
     int u;                  // the row's tile, counted inside the wave
 };
 
-// Fetches the lane's part of trip q (tiles kTiles*q .. of the wave); q >= kTrips fetches nothing.
+// The lane's part of trip q (tiles kTiles*q .. of the wave) as it comes from memory: only the
+// entries the tile's count says are there (these passes are bound by the bytes they pull from the
+// scattered slots: reading whole slots regardless of the counts made them a third slower). The
+// trips of a batch are requested together.
+struct TripRaw { ld_f32x4 a, b; ld_u32x4 xi; };
+constexpr int kAhead = 4;   // trips requested together
+
 template <bool IDX, int ROW>
-__device__ __forceinline__ void trip_fetch(const Ctx& c, int32_t tile0, uint32_t mycnt, int q, Trip& Q) {
-    typedef Rows<ROW> R;
+__device__ __forceinline__ void trip_issue(const Ctx& c, int32_t tile0, uint32_t mycnt, int q, TripRaw& R) {
+    typedef Rows<ROW> RW;
     const int lane = ld_lane();
-    const int u = R::kTiles * (q < R::kTrips ? q : 0) + lane / ROW;
+    const int u = RW::kTiles * q + lane / ROW;
     const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
-    const uint32_t n = (q < R::kTrips && cn <= R::kFast) ? cn : 0u;
+    const uint32_t n = cn <= RW::kFast ? cn : 0u;
     const uint32_t first = static_cast<uint32_t>(lane & (ROW - 1)) * kPerLane;
     const int64_t at = static_cast<int64_t>(tile0 + u) * slot_of<ROW>(c) + first;
-    ld_f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f}, b = {0.0f, 0.0f, 0.0f, 0.0f};
-    ld_u32x4 xi = {0u, 0u, 0u, 0u};
-    if (first < n) a = *reinterpret_cast<const ld_f32x4*>(c.cval + at);
-    if (first + 4 < n) b = *reinterpret_cast<const ld_f32x4*>(c.cval + at + 4);
-    if (IDX && first < n) xi = *reinterpret_cast<const ld_u32x4*>(c.cidx + at);
-    Q.v[0] = a.x; Q.v[1] = a.y; Q.v[2] = a.z; Q.v[3] = a.w;
-    Q.v[4] = b.x; Q.v[5] = b.y; Q.v[6] = b.z; Q.v[7] = b.w;
-    const uint32_t xw[4] = {xi.x, xi.y, xi.z, xi.w};
+    R.a = ld_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    R.b = R.a;
+    R.xi = ld_u32x4{0u, 0u, 0u, 0u};
+    if (first < n) R.a = *reinterpret_cast<const ld_f32x4*>(c.cval + at);
+    if (first + 4 < n) R.b = *reinterpret_cast<const ld_f32x4*>(c.cval + at + 4);
+    if (IDX && first < n) R.xi = *reinterpret_cast<const ld_u32x4*>(c.cidx + at);
+}
+
+template <bool IDX, int ROW>
+__device__ __forceinline__ void trip_finish(const TripRaw& R, uint32_t mycnt, int q, Trip& Q) {
+    typedef Rows<ROW> RW;
+    const int lane = ld_lane();
+    const int u = RW::kTiles * q + lane / ROW;
+    const uint32_t cn = static_cast<uint32_t>(__shfl(static_cast<int>(mycnt), u, LD_WAVE));
+    const uint32_t n = cn <= RW::kFast ? cn : 0u;
+    const uint32_t first = static_cast<uint32_t>(lane & (ROW - 1)) * kPerLane;
+    Q.v[0] = R.a.x; Q.v[1] = R.a.y; Q.v[2] = R.a.z; Q.v[3] = R.a.w;
+    Q.v[4] = R.b.x; Q.v[5] = R.b.y; Q.v[6] = R.b.z; Q.v[7] = R.b.w;
+    if (IDX) {
+        const uint32_t xw[4] = {R.xi.x, R.xi.y, R.xi.z, R.xi.w};
 #pragma unroll
-    for (int j = 0; j < kPerLane; ++j) Q.x[j] = (j & 1) ? (xw[j >> 1] >> 16) : (xw[j >> 1] & 0xFFFFu);
+        for (int j = 0; j < kPerLane; ++j) Q.x[j] = (j & 1) ? (xw[j >> 1] >> 16) : (xw[j >> 1] & 0xFFFFu);
+    }
     Q.have = first < n ? umin(n - first, static_cast<uint32_t>(kPerLane)) : 0u;
     Q.cn = cn;
     Q.u = u;
+}
+
+// Runs body(Q) for every trip of the wave, kAhead trips requested at a time. `first` holds the
+// first batch, requested by the caller as early as it could.
+template <bool IDX, int ROW, class Body>
+__device__ __forceinline__ void for_trips(const Ctx& c, int32_t tile0, uint32_t mycnt, TripRaw (&first)[kAhead],
+                                          Body&& body) {
+    static_assert(Rows<ROW>::kTrips % kAhead == 0, "trips come in whole batches");
+#pragma unroll 1
+    for (int q0 = 0; q0 < Rows<ROW>::kTrips; q0 += kAhead) {
+        if (q0 > 0) {
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) trip_issue<IDX, ROW>(c, tile0, mycnt, q0 + a, first[a]);
+        }
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            Trip Q;
+            trip_finish<IDX, ROW>(first[a], mycnt, q0 + a, Q);
+            body(Q, q0 + a);
+        }
+    }
+}
+
+template <bool IDX, int ROW>
+__device__ __forceinline__ void first_trips(const Ctx& c, int32_t tile0, uint32_t mycnt, TripRaw (&first)[kAhead]) {
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a) trip_issue<IDX, ROW>(c, tile0, mycnt, a, first[a]);
 }
 
 template <bool IDX, int ROW, class Begin, class Item, class End>
@@ -772,7 +880,7 @@ __device__ __forceinline__ void slow_tiles(const Ctx& c, const float* __restrict
 __device__ __forceinline__ void mark_full(const Ctx& c, SegState* st, const GroupRange& gr, uint32_t* list0) {
     if (threadIdx.x == 0) {
         st->mode = kModeFull;
-        *list0 = atomicAdd(c.fail_count, static_cast<uint32_t>(gr.ngroup));
+        *list0 = atomicAdd(c.fail_count + kSyncCount, static_cast<uint32_t>(gr.ngroup));
     }
     __syncthreads();
     for (int32_t q = threadIdx.x; q < gr.ngroup; q += blockDim.x) c.fail_groups[*list0 + q] = gr.group0 + q;
@@ -807,16 +915,18 @@ __global__ __launch_bounds__(kHistGroups * kThreads) void k_hist(const float* __
     const int q = threadIdx.x / kThreads, tid = threadIdx.x % kThreads;
     const int32_t group = blockIdx.x * kHistGroups + q;
     const bool inside = group < c.n_group;
+    const int32_t tile0 = group * kTilesPerGroup + wave_in_group() * kTilesPerWave;
     uint32_t mycnt = 0;
     GroupRange gr;
     gr.k = 0;
+    TripRaw raw[kAhead];
     if (inside) {
         mycnt = wave_counts(c, group);
         gr = group_range(c, group);
+        first_trips<false, ROW>(c, tile0, mycnt, raw);
     }
     const bool live = inside && gr.k != 0;
     const uint32_t tau = gr.tau, binsh = gr.sh;
-    const int32_t tile0 = group * kTilesPerGroup + wave_in_group() * kTilesPerWave;
     for (int b = tid; b < kBins; b += kThreads) lh[q][b] = 0;
     if (tid == 0) qseg[q] = live ? gr.seg : -1;
     __syncthreads();
@@ -824,11 +934,7 @@ __global__ __launch_bounds__(kHistGroups * kThreads) void k_hist(const float* __
         // keys above the binned range all land in the top bin (a third of the candidates, more
         // at higher densities): counted in a register, added once per wave
         uint32_t top = 0;
-        Trip Q, N;
-        trip_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
-#pragma unroll 1
-        for (int i = 0; i < Rows<ROW>::kTrips; ++i) {
-            trip_fetch<false, ROW>(c, tile0, mycnt, i + 1, N);
+        for_trips<false, ROW>(c, tile0, mycnt, raw, [&](const Trip& Q, int) {
 #pragma unroll
             for (int j = 0; j < kPerLane; ++j) {
                 if (static_cast<uint32_t>(j) < Q.have) {
@@ -836,8 +942,7 @@ __global__ __launch_bounds__(kHistGroups * kThreads) void k_hist(const float* __
                     if (bin == static_cast<uint32_t>(kTopBin)) ++top; else atomicAdd(&lh[q][bin], 1u);
                 }
             }
-            Q = N;
-        }
+        });
         slow_tiles<false, ROW>(
             c, r, gr, group, mycnt, tau, [](int) {},
             [&](bool have, float v, uint32_t, bool) {
@@ -960,6 +1065,8 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
     __shared__ uint32_t wsum[2][kWaves];
     const uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
+    TripRaw raw[kAhead];
+    first_trips<false, ROW>(c, blockIdx.x * kTilesPerGroup + (threadIdx.x >> 6) * kTilesPerWave, mycnt, raw);
     SegState* st = c.state + gr.seg;
     const uint32_t mode = st->mode;
     if (gr.k == 0 || mode == kModeFull) return;
@@ -991,11 +1098,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
             wave_ties += t;
         }
     }
-    Trip Q, N;
-    trip_fetch<false, ROW>(c, tile0, mycnt, 0, Q);
-#pragma unroll 1
-    for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
-        trip_fetch<false, ROW>(c, tile0, mycnt, q + 1, N);
+    for_trips<false, ROW>(c, tile0, mycnt, raw, [&](const Trip& Q, int) {
         uint32_t cnt = 0, in = 0;
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
@@ -1039,8 +1142,7 @@ __global__ __launch_bounds__(kThreads) void k_gather(const float* __restrict__ r
             part_gt += cnt;
             part_eq += eqc;
         }
-        Q = N;
-    }
+    });
     uint32_t slow_gt = 0, slow_eq = 0, gt = 0, eq = 0;
     int32_t tile_of_item = 0;
     slow_tiles<false, ROW>(
@@ -1243,6 +1345,8 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     __shared__ float stage_v[kWaves][kTiles * kFast];
     uint32_t mycnt = wave_counts(c, blockIdx.x);
     const GroupRange gr = group_range(c, blockIdx.x);
+    TripRaw raw[kAhead];
+    first_trips<true, ROW>(c, blockIdx.x * kTilesPerGroup + (threadIdx.x >> 6) * kTilesPerWave, mycnt, raw);
     const SegState* st = c.state + gr.seg;
     if (gr.k == 0) return;
     const uint32_t mode = st->mode;
@@ -1252,18 +1356,13 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     const int tl0 = w * kTilesPerWave;
     const int32_t tile0 = blockIdx.x * kTilesPerGroup + tl0;
     int64_t tbase = 0;
-    Trip Q, N;
     if (mode == kModeFull) {
-        trip_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
-#pragma unroll 1
-        for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
-            trip_fetch<true, ROW>(c, tile0, mycnt, q + 1, N);
+        for_trips<true, ROW>(c, tile0, mycnt, raw, [&](const Trip& Q, int) {
             float* rt = r + gr.base + static_cast<int64_t>(tl0 + Q.u) * kTile;
 #pragma unroll
             for (int j = 0; j < kPerLane; ++j)
                 if (static_cast<uint32_t>(j) < Q.have && ld_key(Q.v[j]) >= test) rt[Q.x[j]] = Q.v[j];
-            Q = N;
-        }
+        });
         slow_tiles<true, ROW>(
             c, r, gr, blockIdx.x, mycnt, tau,
             [&](int u) { tbase = gr.base + static_cast<int64_t>(tl0 + u) * kTile; },
@@ -1289,10 +1388,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
     // ties come in index order; keys at or above T pass the filter there.
     const uint32_t keep_from = mode == kModeTies ? T : tau;
     if (mode == kModeTies && lane < kTilesPerWave && tile_take[tl0 + lane] > 0) mycnt = kOverflow;
-    trip_fetch<true, ROW>(c, tile0, mycnt, 0, Q);
-#pragma unroll 1
-    for (int q = 0; q < Rows<ROW>::kTrips; ++q) {
-        trip_fetch<true, ROW>(c, tile0, mycnt, q + 1, N);
+    for_trips<true, ROW>(c, tile0, mycnt, raw, [&](const Trip& Q, int q) {
         const uint32_t out_tile = tile_out[tl0 + Q.u], eq_tile = tile_eqb[tl0 + Q.u];
         uint32_t gtm = 0, eqm = 0;
 #pragma unroll
@@ -1340,8 +1436,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        Q = N;
-    }
+    });
     uint32_t run_out = 0;  // records of the segment emitted before this point
     uint32_t run_eq = 0;   // ties seen before this point
     slow_tiles<true, ROW>(
@@ -1387,11 +1482,8 @@ __device__ __forceinline__ FullRange full_range(const Ctx& c, int32_t g) {
 }
 
 template <int LEVEL>
-__global__ __launch_bounds__(kThreads) void k_full_level(const float* __restrict__ r, Ctx c) {
-    __shared__ uint32_t lh[kBins];
-    __shared__ uint32_t sh[kWaves];
-    __shared__ uint32_t res[2];
-    const uint32_t nlist = *c.fail_count;
+__device__ __forceinline__ void full_level(const float* __restrict__ r, const Ctx& c, uint32_t nlist, uint32_t* lh,
+                                           uint32_t* sh, uint32_t* res) {
     constexpr int match_shift = (LEVEL == 1) ? 31 : (LEVEL == 2 ? kShift1 : kShift2);
     constexpr int digit_shift = (LEVEL == 1) ? kShift1 : (LEVEL == 2 ? kShift2 : 0);
     constexpr uint32_t digit_mask = (LEVEL == 3) ? 0x1FFu : 0x7FFu;
@@ -1427,9 +1519,7 @@ __global__ __launch_bounds__(kThreads) void k_full_level(const float* __restrict
     }
 }
 
-__global__ __launch_bounds__(kThreads) void k_full_count(const float* __restrict__ r, Ctx c) {
-    __shared__ uint32_t sh[kWaves];
-    const uint32_t nlist = *c.fail_count;
+__device__ __forceinline__ void full_count(const float* __restrict__ r, const Ctx& c, uint32_t nlist, uint32_t* sh) {
     for (uint32_t li = blockIdx.x; li < nlist; li += gridDim.x) {
         const int32_t g = c.fail_groups[li];
         const FullRange fr = full_range(c, g);
@@ -1474,10 +1564,9 @@ __global__ __launch_bounds__(kThreads) void k_full_count(const float* __restrict
     }
 }
 
-__global__ __launch_bounds__(kThreads) void k_full_emit(float* __restrict__ r, int32_t* __restrict__ out_idx,
-                                                        float* __restrict__ out_val, Ctx c) {
-    __shared__ uint32_t part[2][kWaves];  // packed (above | ties << 16) per wave
-    const uint32_t nlist = *c.fail_count;
+__device__ __forceinline__ void full_emit(float* __restrict__ r, int32_t* __restrict__ out_idx,
+                                          float* __restrict__ out_val, const Ctx& c, uint32_t nlist,
+                                          uint32_t (*part)[kWaves]) {  // part: packed (above | ties << 16) per wave
     const int lane = ld_lane();
     const int wv = threadIdx.x >> 6;
     for (uint32_t li = blockIdx.x; li < nlist; li += gridDim.x) {
@@ -1538,6 +1627,57 @@ __global__ __launch_bounds__(kThreads) void k_full_emit(float* __restrict__ r, i
     }
 }
 
+// Barrier across the grid of k_full: every workgroup adds one arrival and waits until `target`
+// have come. Needs every workgroup of the grid resident at once (the host sizes the grid for
+// that). The wait is bounded: a workgroup that has polled kSpinLimit times (seconds; a barrier
+// takes microseconds) raises the give-up flag, and every workgroup that sees the flag leaves the
+// kernel, so the grid always drains. Returns false when the kernel is to be left.
+constexpr uint32_t kSpinLimit = 1u << 21;
+
+__device__ __forceinline__ bool grid_barrier(uint32_t* sync, uint32_t target) {
+    __shared__ uint32_t go;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(sync + kSyncArrived, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t ok = 1, spins = 0;
+        while (__hip_atomic_load(sync + kSyncArrived, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            if (__hip_atomic_load(sync + kSyncGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
+                ++spins > kSpinLimit) {
+                __hip_atomic_store(sync + kSyncGaveUp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(64);
+        }
+        go = ok;
+    }
+    __syncthreads();
+    const bool ok = go != 0;
+    if (ok) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __syncthreads();
+    return ok;
+}
+
+// The whole full-segment path in one launch: nothing listed (the usual case), nothing done.
+__global__ __launch_bounds__(kThreads) void k_full(float* __restrict__ r, int32_t* __restrict__ out_idx,
+                                                   float* __restrict__ out_val, Ctx c) {
+    __shared__ uint32_t lh[kBins];
+    __shared__ uint32_t sh[kWaves];
+    __shared__ uint32_t res[2];
+    __shared__ uint32_t part[2][kWaves];
+    const uint32_t nlist = c.fail_count[kSyncCount];
+    if (nlist == 0) return;
+    full_level<1>(r, c, nlist, lh, sh, res);
+    if (!grid_barrier(c.fail_count, 1 * gridDim.x)) return;
+    full_level<2>(r, c, nlist, lh, sh, res);
+    if (!grid_barrier(c.fail_count, 2 * gridDim.x)) return;
+    full_level<3>(r, c, nlist, lh, sh, res);
+    if (!grid_barrier(c.fail_count, 3 * gridDim.x)) return;
+    full_count(r, c, nlist, sh);
+    if (!grid_barrier(c.fail_count, 4 * gridDim.x)) return;
+    full_emit(r, out_idx, out_val, c, nlist, part);
+}
+
 // ---------------------------------------------------------------- host side
 
 struct Layout {
@@ -1563,7 +1703,7 @@ Layout layout(int32_t n_seg, int64_t n_group, int32_t slot) {
     L.gkey = take(4 * gather_entries);
     L.gtile = take(4 * gather_entries);
     L.fail_groups = take(4 * ng);
-    L.fail_count = take(4);
+    L.fail_count = take(4 * kSyncWords);
     L.cval = take(4 * nt * static_cast<size_t>(slot));  // the two arrays whose size depends on `slot` come last
     L.cidx = take(2 * nt * static_cast<size_t>(slot));
     L.total = o;
@@ -1605,6 +1745,110 @@ int32_t wanted_slot(int32_t n_seg, const int64_t* seg_off, const int32_t* seg_k,
     if (slot < kSlotMin) slot = kSlotMin;
     if (slot > kSlotMax) slot = kSlotMax;
     return static_cast<int32_t>(slot);
+}
+
+Ctx make_ctx(void* workspace, const Layout& L, int32_t n_seg, int64_t n_group, int32_t slot) {
+    char* ws = static_cast<char*>(workspace);
+    Ctx c;
+    c.desc = reinterpret_cast<SegDesc*>(ws + L.desc);
+    c.gdesc = reinterpret_cast<GroupDesc*>(ws + L.gdesc);
+    c.state = reinterpret_cast<SegState*>(ws + L.state);
+    c.hist = reinterpret_cast<uint32_t*>(ws + L.hist);
+    c.cnt = reinterpret_cast<uint32_t*>(ws + L.cnt);
+    c.cval = reinterpret_cast<float*>(ws + L.cval);
+    c.cidx = reinterpret_cast<uint16_t*>(ws + L.cidx);
+    c.tile_gt = reinterpret_cast<uint32_t*>(ws + L.tile_gt);
+    c.tile_eq = reinterpret_cast<uint32_t*>(ws + L.tile_eq);
+    c.group_gt = reinterpret_cast<uint32_t*>(ws + L.group_gt);
+    c.group_eq = reinterpret_cast<uint32_t*>(ws + L.group_eq);
+    c.gkey = reinterpret_cast<uint32_t*>(ws + L.gkey);
+    c.gtile = reinterpret_cast<int32_t*>(ws + L.gtile);
+    c.fail_groups = reinterpret_cast<int32_t*>(ws + L.fail_groups);
+    c.fail_count = reinterpret_cast<uint32_t*>(ws + L.fail_count);
+    c.n_seg = n_seg;
+    c.n_group = static_cast<int32_t>(n_group);
+    c.slot = slot;
+    return c;
+}
+
+// One workgroup per segment: the path the last call took for it, and how many of its tiles
+// overflowed their candidate slot.
+__global__ __launch_bounds__(kThreads) void k_paths(Ctx c, int32_t* __restrict__ paths, int32_t* __restrict__ overflowed) {
+    __shared__ uint32_t sh[kWaves];
+    const int32_t s = blockIdx.x;
+    const SegDesc d = c.desc[s], dn = c.desc[s + 1];
+    uint32_t over = 0;
+    if (d.k > 0) {
+        const int64_t t0 = static_cast<int64_t>(d.group0) * kTilesPerGroup, t1 = static_cast<int64_t>(dn.group0) * kTilesPerGroup;
+        for (int64_t t = t0 + threadIdx.x; t < t1; t += kThreads) over += c.cnt[t] == kOverflow;
+    }
+    uint32_t total;
+    block_escan<kThreads>(over, sh, total);
+    if (threadIdx.x == 0) {
+        const SegState st = c.state[s];
+        paths[s] = static_cast<int32_t>(st.mode | (st.tied ? 0x100u : 0u) |
+                                        (c.fail_count[kSyncGaveUp] ? 0x10000u : 0u));
+        if (overflowed) overflowed[s] = static_cast<int32_t>(total);
+    }
+}
+
+// Packs the segment table for k_prep's arguments; false when it has too many segments or too
+// many distinct (length, k) pairs.
+bool pack_table(int32_t n_seg, const int64_t* seg_off, const int32_t* seg_k, PackedTable& pt) {
+    pt.n_seg = 0;
+    if (n_seg > kDictSegs) return false;
+    int used = 0, last = 0;
+    for (int32_t s = 0; s < n_seg; ++s) {
+        const uint32_t len = static_cast<uint32_t>(seg_off[s + 1] - seg_off[s]), k = static_cast<uint32_t>(seg_k[s]);
+        int code = -1;
+        if (used > 0 && pt.len[last] == len && pt.k[last] == k) code = last;  // runs of equal tensors are common
+        for (int d = 0; code < 0 && d < used; ++d)
+            if (pt.len[d] == len && pt.k[d] == k) code = d;
+        if (code < 0) {
+            if (used == kDictMax) return false;
+            code = used++;
+            pt.len[code] = len;
+            pt.k[code] = k;
+        }
+        pt.code[s] = static_cast<uint8_t>(code);
+        last = code;
+    }
+    int64_t out0 = 0, group0 = 0;
+    for (int32_t b = 0; b < kDictSegs / LD_WAVE; ++b) {
+        const int32_t s0 = b * LD_WAVE < n_seg ? b * LD_WAVE : n_seg;
+        pt.off0[b] = static_cast<uint32_t>(seg_off[s0]);
+        pt.out0[b] = static_cast<uint32_t>(out0);
+        pt.group0[b] = static_cast<uint32_t>(group0);
+        for (int32_t s = s0; s < n_seg && s < s0 + LD_WAVE; ++s) {
+            out0 += seg_k[s];
+            group0 += groups_of(seg_off[s], seg_off[s + 1]);
+        }
+    }
+    for (int d = used; d < kDictMax; ++d) pt.len[d] = pt.k[d] = 0;
+    for (int32_t s = n_seg; s < kDictSegs; ++s) pt.code[s] = 0;
+    pt.n_seg = n_seg;
+    return true;
+}
+
+// Workgroups of k_full that the current device keeps resident at once, halved to leave room for
+// whatever else runs (looked up once per device: a property of the device and of the kernel, not
+// state of a call). 0 on failure.
+int32_t full_grid_limit() {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int32_t> limit[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    int32_t v = limit[dev].load(std::memory_order_acquire);
+    if (v == 0) {
+        int cus = 0, per_cu = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_full, kThreads, 0) != hipSuccess) return 0;
+        if (cus <= 0 || per_cu <= 0) return 0;
+        const int64_t all = static_cast<int64_t>(cus) * per_cu / 2;
+        v = static_cast<int32_t>(all < 1 ? 1 : (all > kFullGrid ? kFullGrid : all));
+        limit[dev].store(v, std::memory_order_release);
+    }
+    return v;
 }
 
 }  // namespace
@@ -1652,29 +1896,13 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
     const Layout L = layout(n_seg, n_group, slot);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    char* ws = static_cast<char*>(workspace);
-    Ctx c;
-    c.desc = reinterpret_cast<SegDesc*>(ws + L.desc);
-    c.gdesc = reinterpret_cast<GroupDesc*>(ws + L.gdesc);
-    c.state = reinterpret_cast<SegState*>(ws + L.state);
-    c.hist = reinterpret_cast<uint32_t*>(ws + L.hist);
-    c.cnt = reinterpret_cast<uint32_t*>(ws + L.cnt);
-    c.cval = reinterpret_cast<float*>(ws + L.cval);
-    c.cidx = reinterpret_cast<uint16_t*>(ws + L.cidx);
-    c.tile_gt = reinterpret_cast<uint32_t*>(ws + L.tile_gt);
-    c.tile_eq = reinterpret_cast<uint32_t*>(ws + L.tile_eq);
-    c.group_gt = reinterpret_cast<uint32_t*>(ws + L.group_gt);
-    c.group_eq = reinterpret_cast<uint32_t*>(ws + L.group_eq);
-    c.gkey = reinterpret_cast<uint32_t*>(ws + L.gkey);
-    c.gtile = reinterpret_cast<int32_t*>(ws + L.gtile);
-    c.fail_groups = reinterpret_cast<int32_t*>(ws + L.fail_groups);
-    c.fail_count = reinterpret_cast<uint32_t*>(ws + L.fail_count);
-    c.n_seg = n_seg;
-    c.n_group = static_cast<int32_t>(n_group);
-    c.slot = slot;
+    const Ctx c = make_ctx(workspace, L, n_seg, n_group, slot);
 
-    // segment table travels as kernel arguments, kSegPerLaunch segments per launch
-    {
+    ld_begin_call();
+    // The segment table travels as kernel arguments: packed into k_prep's own when it has few
+    // distinct (length, k) pairs, else through k_upload launches of kSegPerLaunch segments each.
+    PackedTable pt;
+    if (!pack_table(n_seg, seg_off, seg_k, pt)) {
         int64_t out0 = 0;
         int32_t group0 = 0;
         for (int32_t s0 = 0; s0 < n_seg; s0 += kSegPerLaunch) {
@@ -1700,7 +1928,7 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
     }
     const dim3 block(kThreads);
     const dim3 sgrid(static_cast<uint32_t>(n_seg));
-    k_prep<<<sgrid, dim3(kPrepThreads), 0, st>>>(grad, residual, c, strategy == LD_COMPRESS_FULL ? 1 : 0);
+    k_prep<<<sgrid, dim3(kPrepThreads), 0, st>>>(grad, residual, c, strategy == LD_COMPRESS_FULL ? 1 : 0, pt);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (n_group == 0) return LD_OK;
     const dim3 grid(static_cast<uint32_t>(n_group));
@@ -1715,22 +1943,43 @@ extern "C" ld_status ld_compress_topk_strategy(const float* grad, float* residua
     if (row == 16) k_hist<16><<<hgrid, hblock, 0, st>>>(residual, c);
     else if (row == 32) k_hist<32><<<hgrid, hblock, 0, st>>>(residual, c);
     else k_hist<64><<<hgrid, hblock, 0, st>>>(residual, c);
+    if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     k_bin<<<sgrid, block, 0, st>>>(c);
+    if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (row == 16) k_gather<16><<<grid, block, 0, st>>>(residual, c);
     else if (row == 32) k_gather<32><<<grid, block, 0, st>>>(residual, c);
     else k_gather<64><<<grid, block, 0, st>>>(residual, c);
+    if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     k_select<<<sgrid, block, 0, st>>>(c);
+    if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     if (row == 16) k_emit<16><<<grid, block, 0, st>>>(residual, out_idx, out_val, c);
     else if (row == 32) k_emit<32><<<grid, block, 0, st>>>(residual, out_idx, out_val, c);
     else k_emit<64><<<grid, block, 0, st>>>(residual, out_idx, out_val, c);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
-    // segments handed to the full path (normally none: these exit at once)
-    const dim3 fgrid(static_cast<uint32_t>(n_group < kFullGrid ? n_group : kFullGrid));
-    k_full_level<1><<<fgrid, block, 0, st>>>(residual, c);
-    k_full_level<2><<<fgrid, block, 0, st>>>(residual, c);
-    k_full_level<3><<<fgrid, block, 0, st>>>(residual, c);
-    k_full_count<<<fgrid, block, 0, st>>>(residual, c);
-    k_full_emit<<<fgrid, block, 0, st>>>(residual, out_idx, out_val, c);
+    // segments handed to the full path (normally none: the launch returns at once). Its grid must be
+    // resident as a whole (the phases hand over through a barrier across it).
+    const int32_t resident = full_grid_limit();
+    if (resident <= 0) return LD_ERR_HIP;
+    const dim3 fgrid(static_cast<uint32_t>(n_group < resident ? n_group : resident));
+    k_full<<<fgrid, block, 0, st>>>(residual, out_idx, out_val, c);
+    return ld_launch_status();
+}
+
+extern "C" ld_status ld_compress_topk_paths(const void* workspace, size_t workspace_bytes, int32_t n_seg,
+                                            const int64_t* seg_off, int32_t* paths, int32_t* overflowed_tiles,
+                                            ld_stream stream) {
+    if (n_seg < 0) return LD_ERR_RANGE;
+    if (n_seg == 0) return LD_OK;
+    if (!seg_off || !paths) return LD_ERR_NULL;
+    const int64_t n_group = count_groups(n_seg, seg_off);
+    if (n_group < 0 || n_group > INT32_MAX / kTilesPerGroup) return LD_ERR_RANGE;
+    if (!ld_aligned(paths, 4) || !ld_aligned(overflowed_tiles, 4)) return LD_ERR_ALIGN;
+    const Layout L = layout(n_seg, n_group, kSlotMin);  // the slot size only moves the candidate arrays
+    if (!workspace || !ld_aligned(workspace, 256) || workspace_bytes < L.total) return LD_ERR_WORKSPACE;
+    const Ctx c = make_ctx(const_cast<void*>(workspace), L, n_seg, n_group, kSlotMin);
+    ld_begin_call();
+    k_paths<<<dim3(static_cast<uint32_t>(n_seg)), dim3(kThreads), 0, static_cast<hipStream_t>(stream)>>>(
+        c, paths, overflowed_tiles);
     return ld_launch_status();
 }
 

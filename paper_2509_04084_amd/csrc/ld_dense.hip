@@ -173,6 +173,7 @@ extern "C" ld_status ld_snapshot_layer(const void* grad_bf16, void* snap_bf16, i
     const int64_t bytes = n_elems * 2;
     const int64_t blocks = (bytes + kCopyBlockBytes - 1) / kCopyBlockBytes;
     if (blocks > INT32_MAX - 8) return LD_ERR_RANGE;
+    ld_begin_call();
     k_snapshot<<<dim3(static_cast<uint32_t>((blocks + 7) / 8 * 8)), dim3(kCopyThreads), 0,
                  static_cast<hipStream_t>(stream)>>>(static_cast<const unsigned char*>(grad_bf16),
                                                      static_cast<unsigned char*>(snap_bf16), bytes);
@@ -190,6 +191,7 @@ extern "C" ld_status ld_snapshot_layers(const void* const* src, void* const* dst
         if (!ld_aligned(src[l], 2) || !ld_aligned(dst[l], 2)) return LD_ERR_ALIGN;
         if ((n_elems[l] * 2 + kCopyBlockBytes - 1) / kCopyBlockBytes > (1 << 30)) return LD_ERR_RANGE;
     }
+    ld_begin_call();
     int32_t l = 0;
     while (l < n_layers) {
         CopyBatch cb;
@@ -242,6 +244,7 @@ extern "C" ld_status ld_merge_dense_adam(float* w, float* m, float* v, int64_t n
     if (blocks > INT32_MAX - 8) return LD_ERR_RANGE;
     const dim3 grid(static_cast<uint32_t>((blocks + 7) / 8 * 8)), block(kAdamThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    ld_begin_call();
     // steps are fused four (or eight) at a time; the state round-trips through fp32
     // memory between passes, which is exactly what it does between two calls
     int t0 = 0;

@@ -220,15 +220,17 @@ extern "C" size_t ld_merge_sparse_workspace(int64_t n, int32_t W, const int64_t*
     return ld_round_up(static_cast<size_t>(group) * (static_cast<size_t>(chunks(n)) + 1) * 4, 256);
 }
 
-extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t* const* idx,
-                                              const float* const* val, const int64_t* K, int32_t W,
-                                              float lr, void* workspace, size_t workspace_bytes,
-                                              ld_stream stream, int32_t strategy) {
+namespace {
+
+ld_status merge_sparse_impl(float* w, int64_t n, const int32_t* const* idx, const float* const* val,
+                            const int64_t* K, int32_t W, float lr, void* workspace, size_t workspace_bytes,
+                            ld_stream stream, int32_t strategy) {
     const ld_status st = check_diff_args(w, n, idx, val, K, W);
     if (st != LD_OK) return st;
     if (strategy < LD_MERGE_AUTO || strategy > LD_MERGE_SCATTER) return LD_ERR_RANGE;
     if (W == 0 || n == 0) return LD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    ld_begin_call();
 
     int64_t total = 0;
     for (int32_t t = 0; t < W; ++t) total += K[t];
@@ -279,6 +281,15 @@ extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     }
     return LD_OK;
+}
+
+}  // namespace
+
+extern "C" ld_status ld_merge_sparse_strategy(float* w, int64_t n, const int32_t* const* idx,
+                                              const float* const* val, const int64_t* K, int32_t W,
+                                              float lr, void* workspace, size_t workspace_bytes,
+                                              ld_stream stream, int32_t strategy) {
+    return merge_sparse_impl(w, n, idx, val, K, W, lr, workspace, workspace_bytes, stream, strategy);
 }
 
 extern "C" ld_status ld_merge_sparse(float* w, int64_t n, const int32_t* const* idx,

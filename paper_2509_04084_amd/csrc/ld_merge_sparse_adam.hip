@@ -208,6 +208,7 @@ extern "C" ld_status ld_merge_sparse_adam(float* w, float* m, float* v, int64_t 
         workspace_bytes < ld_merge_sparse_adam_workspace(n, W, K))
         return LD_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    ld_begin_call();
     const int32_t nsub = static_cast<int32_t>((n + kSub - 1) / kSub), nchunk = chunks(n);
     int32_t* ctab = static_cast<int32_t*>(workspace);
     static_assert(kGroupMax <= LD_MAX_ADAM_STEPS, "step table too small");

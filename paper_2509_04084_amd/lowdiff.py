@@ -60,6 +60,8 @@ def load() -> ctypes.CDLL:
     lib.ld_compress_topk.restype = i32
     lib.ld_compress_topk_strategy.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, sz, vp, i32]
     lib.ld_compress_topk_strategy.restype = i32
+    lib.ld_compress_topk_paths.argtypes = [vp, sz, i32, vp, vp, vp, vp]
+    lib.ld_compress_topk_paths.restype = i32
     lib.ld_snapshot_layer.argtypes = [vp, vp, i64, vp]
     lib.ld_snapshot_layer.restype = i32
     lib.ld_snapshot_layers.argtypes = [vp, vp, vp, i32, vp]
@@ -114,6 +116,28 @@ def _dev(t: Optional[torch.Tensor], dtype, name: str) -> ctypes.c_void_p:
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _same_device(*tensors) -> None:
+    devs = {t.device for t in tensors if t is not None}
+    if len(devs) > 1:
+        raise ValueError(f"tensors lie on different devices: {sorted(map(str, devs))}")
+
+
+def _record(t: torch.Tensor, *streams) -> torch.Tensor:
+    """Marks a tensor the binding allocated as in use on the streams the library writes it on."""
+    for st in streams:
+        if st is not None and t.is_cuda:
+            t.record_stream(st)
+    return t
+
+
+def _scratch(nbytes: int, device, *streams) -> torch.Tensor:
+    """A temporary the binding allocates itself and drops when the call returns. The kernels that use
+    it run on `streams`, which need not be the stream torch's caching allocator ties the block to:
+    the block is marked as in use on each of them, so that it is not handed out again before they
+    have passed this point."""
+    return _record(torch.empty(max(1, int(nbytes)), dtype=torch.uint8, device=device), *streams)
+
+
 def _host(a, dtype) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=dtype)
 
@@ -145,16 +169,19 @@ def ld_compress_topk(grad: torch.Tensor, residual: torch.Tensor, seg_off, seg_k,
     n_seg = int(seg_k.shape[0])
     if seg_off.shape[0] != n_seg + 1:
         raise ValueError("seg_off must have n_seg + 1 entries")
+    if int(seg_off[-1]) != grad.numel() or grad.numel() != residual.numel():
+        raise ValueError(f"segment table covers {int(seg_off[-1])} elements, grad has {grad.numel()}, "
+                         f"residual has {residual.numel()}")
+    _same_device(grad, residual, out_idx, out_val, workspace)
     K = int(seg_k.astype(np.int64).sum())
     if out_idx is None:
-        out_idx = torch.empty(K, dtype=torch.int32, device=grad.device)
+        out_idx = _record(torch.empty(K, dtype=torch.int32, device=grad.device), stream)
     if out_val is None:
-        out_val = torch.empty(K, dtype=torch.float32, device=grad.device)
+        out_val = _record(torch.empty(K, dtype=torch.float32, device=grad.device), stream)
     if out_idx.numel() < K or out_val.numel() < K:
         raise ValueError("output buffers smaller than sum(seg_k)")
     if workspace is None:
-        workspace = torch.empty(max(1, int(lib.ld_compress_topk_workspace_for(n_seg, _hp(seg_off), _hp(seg_k)))),
-                                dtype=torch.uint8, device=grad.device)
+        workspace = _scratch(lib.ld_compress_topk_workspace_for(n_seg, _hp(seg_off), _hp(seg_k)), grad.device, stream)
     st = lib.ld_compress_topk_strategy(
         _dev(grad, torch.float32, "grad"), _dev(residual, torch.float32, "residual"),
         _hp(seg_off), _hp(seg_k), n_seg,
@@ -162,6 +189,23 @@ def ld_compress_topk(grad: torch.Tensor, residual: torch.Tensor, seg_off, seg_k,
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream), int(strategy))
     _check("ld_compress_topk", st)
     return out_idx, out_val
+
+
+LD_PATH_CANDIDATES, LD_PATH_FULL, LD_PATH_TIES = 0, 1, 2
+
+
+def ld_compress_topk_paths(workspace: torch.Tensor, seg_off, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(paths, overflowed_tiles), int32 device tensors of one entry per segment: which way the last
+    ld_compress_topk call that used `workspace` took for each segment (see lowdiff.h)."""
+    seg_off = _host(seg_off, np.int64)
+    n_seg = int(seg_off.shape[0]) - 1
+    paths = torch.empty(max(n_seg, 1), dtype=torch.int32, device=workspace.device)
+    over = torch.empty(max(n_seg, 1), dtype=torch.int32, device=workspace.device)
+    st = load().ld_compress_topk_paths(_dev(workspace, torch.uint8, "workspace"), workspace.numel(), n_seg,
+                                       _hp(seg_off), _dev(paths, torch.int32, "paths"),
+                                       _dev(over, torch.int32, "overflowed_tiles"), _stream(stream))
+    _check("ld_compress_topk_paths", st)
+    return paths[:n_seg], over[:n_seg]
 
 
 def _dev_or_pinned(t: torch.Tensor, dtype, name: str) -> ctypes.c_void_p:
@@ -215,11 +259,11 @@ def ld_merge_sparse(w: torch.Tensor, idx: Sequence[torch.Tensor], val: Sequence[
     for a, b in zip(idx, val):
         if a.numel() != b.numel():
             raise ValueError("idx[t] and val[t] differ in size")
+    _same_device(w, workspace, *idx, *val)
     ip = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.int32, "idx").value or 0 for t in idx])
     vp = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.float32, "val").value or 0 for t in val])
     if workspace is None:
-        workspace = torch.empty(int(lib.ld_merge_sparse_workspace(w.numel(), W, _hp(K))),
-                                dtype=torch.uint8, device=w.device)
+        workspace = _scratch(lib.ld_merge_sparse_workspace(w.numel(), W, _hp(K)), w.device, stream)
     st = lib.ld_merge_sparse_strategy(_dev(w, torch.float32, "w"), w.numel(), ip, vp, _hp(K), W,
                                       ctypes.c_float(lr), _dev(workspace, torch.uint8, "workspace"),
                                       workspace.numel(), _stream(stream), int(strategy))
@@ -230,9 +274,12 @@ def ld_merge_dense_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grads
                         step0: int, lr: float, beta1: float, beta2: float, eps: float, stream=None) -> None:
     """Replays the bf16 gradients as Adam steps step0+1.. onto (w, m, v), in place."""
     W = len(grads_bf16)
+    if m.numel() != w.numel() or v.numel() != w.numel():
+        raise ValueError("w, m, v differ in size")
     for g in grads_bf16:
         if g.numel() != w.numel():
             raise ValueError("gradient and parameter sizes differ")
+    _same_device(w, m, v, *grads_bf16)
     gp = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.bfloat16, "grad").value or 0 for t in grads_bf16])
     st = load().ld_merge_dense_adam(_dev(w, torch.float32, "w"), _dev(m, torch.float32, "m"),
                                     _dev(v, torch.float32, "v"), w.numel(), gp, W, int(step0),
@@ -260,11 +307,11 @@ def ld_merge_sparse_from_host(w: torch.Tensor, idx: Sequence[torch.Tensor], val:
     n = w.numel()
     group = max(1, min(int(group), 64))
     if staging is None:
-        staging = torch.empty(max(256, int(lib.ld_merge_sparse_from_host_staging(_hp(K), W, group))),
-                              dtype=torch.uint8, device=w.device)
+        staging = _scratch(max(256, int(lib.ld_merge_sparse_from_host_staging(_hp(K), W, group))), w.device,
+                           copy_stream, merge_stream)
     if workspace is None:
-        workspace = torch.empty(max(256, int(lib.ld_merge_sparse_workspace(n, min(group, max(W, 1)), _hp(K)))),
-                                dtype=torch.uint8, device=w.device)
+        workspace = _scratch(max(256, int(lib.ld_merge_sparse_workspace(n, min(group, max(W, 1)), _hp(K)))),
+                             w.device, copy_stream, merge_stream)
     ip = (ctypes.c_void_p * max(W, 1))(*[t.data_ptr() for t in idx])
     vp = (ctypes.c_void_p * max(W, 1))(*[t.data_ptr() for t in val])
     st = lib.ld_merge_sparse_from_host(_dev(w, torch.float32, "w"), n, ip, vp, _hp(K), W, ctypes.c_float(lr), group,
@@ -309,11 +356,11 @@ def ld_merge_sparse_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, idx:
     for a, b in zip(idx, val):
         if a.numel() != b.numel():
             raise ValueError("idx[t] and val[t] differ in size")
+    _same_device(w, m, v, workspace, *idx, *val)
     ip = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.int32, "idx").value or 0 for t in idx])
     vp = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.float32, "val").value or 0 for t in val])
     if workspace is None:
-        workspace = torch.empty(int(lib.ld_merge_sparse_adam_workspace(w.numel(), W, _hp(K))),
-                                dtype=torch.uint8, device=w.device)
+        workspace = _scratch(lib.ld_merge_sparse_adam_workspace(w.numel(), W, _hp(K)), w.device, stream)
     st = lib.ld_merge_sparse_adam(_dev(w, torch.float32, "w"), _dev(m, torch.float32, "m"),
                                   _dev(v, torch.float32, "v"), w.numel(), ip, vp, _hp(K), W, int(step0),
                                   ctypes.c_float(lr), ctypes.c_float(beta1), ctypes.c_float(beta2),
@@ -341,16 +388,17 @@ def ld_combine_sparse(idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], 
     dev = idx[0].device if N else torch.device("cuda", torch.cuda.current_device())
     total = int(K.sum())
     if out_idx is None:
-        out_idx = torch.empty(total, dtype=torch.int32, device=dev)
+        out_idx = _record(torch.empty(total, dtype=torch.int32, device=dev), stream)
     if out_val is None:
-        out_val = torch.empty(total, dtype=torch.float32, device=dev)
+        out_val = _record(torch.empty(total, dtype=torch.float32, device=dev), stream)
     if out_count is None:
-        out_count = torch.empty(1, dtype=torch.int64, device=dev)
+        out_count = _record(torch.empty(1, dtype=torch.int64, device=dev), stream)
     cap = min(out_idx.numel(), out_val.numel())
+    _same_device(out_idx, out_val, out_count, workspace, *idx, *val)
     ip = (ctypes.c_void_p * max(N, 1))(*[_dev(t, torch.int32, "idx").value or 0 for t in idx])
     vp = (ctypes.c_void_p * max(N, 1))(*[_dev(t, torch.float32, "val").value or 0 for t in val])
     if workspace is None:
-        workspace = torch.empty(int(lib.ld_combine_sparse_workspace(int(n), N)), dtype=torch.uint8, device=dev)
+        workspace = _scratch(lib.ld_combine_sparse_workspace(int(n), N), dev, stream)
     st = lib.ld_combine_sparse(ip, vp, _hp(K), N, int(n), ctypes.c_float(scale),
                                _dev(out_idx, torch.int32, "out_idx"), _dev(out_val, torch.float32, "out_val"),
                                cap, _dev(out_count, torch.int64, "out_count"),

@@ -1,9 +1,9 @@
 #!/usr/bin/env python3
 """Per-kernel text summary of a rocprofv3 result database (``*_results.db``).
 
-    python3 -m paper_2509_04084_amd.rocprof_summary trace  <db>            # --kernel-trace run
-    python3 -m paper_2509_04084_amd.rocprof_summary pmc    <db> [<db> ..]  # --pmc runs (one counter each)
-    python3 -m paper_2509_04084_amd.rocprof_summary traffic <sparse pmc summary> <dense pmc summary>
+    python3 rocprof_summary.py trace  <db>            # --kernel-trace run
+    python3 rocprof_summary.py pmc    <db> [<db> ..]  # --pmc runs (one counter each)
+    python3 rocprof_summary.py traffic <sparse pmc summary> <dense pmc summary>
 
 ``trace`` prints calls / total / average / min / max duration per kernel of this
 library (kernels of other libraries, e.g. the input generators, are left out
@@ -20,7 +20,7 @@ from __future__ import annotations
 import sqlite3
 import sys
 
-OURS = ("k_main", "k_prep", "k_upload", "k_hist", "k_bin", "k_gather", "k_select", "k_emit", "k_full_",
+OURS = ("k_main", "k_prep", "k_upload", "k_hist", "k_bin", "k_gather", "k_select", "k_emit", "k_full", "k_paths",
         "k_chunks", "k_merge_", "k_sparse_adam", "k_combine_", "k_snapshot", "k_adam")
 
 
@@ -63,7 +63,7 @@ def pmc(db_paths) -> str:
 
 
 # kernel-name prefixes (template arguments follow some of them)
-COMPRESS_KERNELS = ("k_upload", "k_prep", "k_main", "k_hist", "k_bin", "k_gather", "k_select", "k_emit", "k_full_")
+COMPRESS_KERNELS = ("k_upload", "k_prep", "k_main", "k_hist", "k_bin", "k_gather", "k_select", "k_emit", "k_full")
 
 
 def _table(path):

@@ -234,3 +234,46 @@ def test_missing_library_fails_loudly(tmp_path, monkeypatch):
         ld.load()
     with pytest.raises(RuntimeError):
         ld.ld_compress_topk_workspace(np.array([0, 10], np.int64))
+
+
+def test_binding_refuses_mismatched_sizes_and_devices_before_any_launch():
+    # The C ABI cannot know how large the caller's buffers are; the binding can, and must refuse
+    # what would make a kernel run past an allocation. Nothing is launched (no GPU here).
+    import torch
+    off = np.array([0, 100, 300], np.int64)
+    k = np.array([1, 2], np.int32)
+    g, r = torch.zeros(300), torch.zeros(300)
+    with pytest.raises(ValueError, match="segment table covers"):
+        ld.ld_compress_topk(torch.zeros(299), torch.zeros(299), off, k)     # table longer than the tensors
+    with pytest.raises(ValueError, match="segment table covers"):
+        ld.ld_compress_topk(g, torch.zeros(301), off, k)                    # residual of another size
+    with pytest.raises(ValueError, match="different devices"):
+        ld.ld_compress_topk(g, torch.zeros(300, device="meta"), off, k)
+    w = torch.zeros(64)
+    gb = [torch.zeros(64, dtype=torch.bfloat16)]
+    with pytest.raises(ValueError, match="w, m, v differ"):
+        ld.ld_merge_dense_adam(w, torch.zeros(63), torch.zeros(64), gb, 0, 1e-4, 0.9, 0.999, 1e-8)
+    with pytest.raises(ValueError, match="w, m, v differ"):
+        ld.ld_merge_dense_adam(w, torch.zeros(64), torch.zeros(65), gb, 0, 1e-4, 0.9, 0.999, 1e-8)
+    with pytest.raises(ValueError, match="sizes differ"):
+        ld.ld_merge_dense_adam(w, torch.zeros(64), torch.zeros(64), [torch.zeros(60, dtype=torch.bfloat16)],
+                               0, 1e-4, 0.9, 0.999, 1e-8)
+    with pytest.raises(ValueError, match="different devices"):
+        ld.ld_merge_dense_adam(w, torch.zeros(64, device="meta"), torch.zeros(64), gb, 0, 1e-4, 0.9, 0.999, 1e-8)
+    with pytest.raises(ValueError, match="w, m, v differ"):
+        ld.ld_merge_sparse_adam(w, torch.zeros(63), torch.zeros(64), [], [], 0, 1e-4, 0.9, 0.999, 1e-8)
+    i, v = torch.zeros(4, dtype=torch.int32), torch.zeros(4)
+    with pytest.raises(ValueError, match="different devices"):
+        ld.ld_merge_sparse(w, [i], [torch.zeros(4, device="meta")], 0.1)
+
+
+def test_compress_paths_argument_errors():
+    lib = ld.load()
+    V = ctypes.c_void_p
+    off = np.array([0, 100, 300], np.int64)
+    wsb = lib.ld_compress_topk_workspace(2, _p(off))
+    assert lib.ld_compress_topk_paths(V(FAKE), wsb, 2, _p(off), V(0), V(0), V(0)) == -1
+    assert lib.ld_compress_topk_paths(V(FAKE), wsb - 1, 2, _p(off), V(FAKE), V(0), V(0)) == -3
+    assert lib.ld_compress_topk_paths(V(0), wsb, 2, _p(off), V(FAKE), V(0), V(0)) == -3
+    assert lib.ld_compress_topk_paths(V(FAKE), wsb, -1, _p(off), V(FAKE), V(0), V(0)) == -2
+    assert lib.ld_compress_topk_paths(V(FAKE), wsb, 0, _p(off), V(FAKE), V(0), V(0)) == 0

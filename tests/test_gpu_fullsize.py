@@ -34,7 +34,8 @@ def test_gpt2xl_compress_and_merge_full_size():
     off, k = wl.seg_off, wl.seg_k
     n, n_seg = wl.n, len(wl.sizes)
     K = int(k.astype(np.int64).sum())
-    W = 3  # diffs built here (the benchmark chains 20 the same way)
+    W = 3  # diffs built here by chained compress calls (the benchmark chains 20 the same way); the
+    # merged window below is the configuration's 20 diffs: these 3 plus 17 random ascending lists
     out0 = np.concatenate([[0], np.cumsum(k.astype(np.int64))])
     # segments redone by the oracle: the first small ones, one of every size class, the last
     sample = sorted({1, 2, 3, 4, 5, 6, 10, 12, 13, n_seg - 3, n_seg - 2, n_seg - 1})
@@ -80,13 +81,28 @@ def test_gpt2xl_compress_and_merge_full_size():
             np.testing.assert_array_equal(bits(val[o0:o1].cpu().numpy()), bits(ov), err_msg=f"val seg {s} t={t}")
             np.testing.assert_array_equal(bits(r[lo:hi].cpu().numpy()), bits(orr), err_msg=f"residual seg {s} t={t}")
         del g, r_before
-    # --- merge of the window, checked by the oracle on slices of w
-    _progress("merge")
+    # --- the rest of the 20-diff window: random ascending lists of K records each, same value law
+    _progress("drawing 17 more diffs")
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(404)
+    for t in range(W, wl.window):
+        u = torch.unique(torch.randint(0, n, (K + K // 50,), device=DEV, generator=gen, dtype=torch.int64))
+        assert u.numel() >= K
+        keep = torch.ones(u.numel(), dtype=torch.bool, device=DEV)
+        keep[torch.randperm(u.numel(), device=DEV, generator=gen)[: u.numel() - K]] = False
+        idxs.append(u[keep].to(torch.int32))
+        vals.append(synth._draw("student3", K, gen, DEV, wl.scale))
+        del u, keep
+    assert len(idxs) == wl.window == 20 and all(i.numel() == K for i in idxs)
+    # --- merge of the window as the benchmark launches it (one call, one workspace), checked by the
+    #     oracle on slices of w
+    _progress("merge of the 20-diff window")
     w = synth.base_weights(n, device=DEV, std=wl.w_std)
     slices = [(0, 3_000_000), (int(off[3]) - 1_000_000, int(off[3]) + 2_000_000),
               (n // 2 - 1_234_567, n // 2 + 1_000_000), (n - 2_500_001, n)]
     before = [w[a:b].cpu().numpy() for a, b in slices]
-    ld.ld_merge_sparse(w, idxs, vals, wl.lr)
+    ws_m = torch.empty(ld.ld_merge_sparse_workspace(n, [K] * wl.window), dtype=torch.uint8, device=DEV)
+    ld.ld_merge_sparse(w, idxs, vals, wl.lr, ws_m)
     torch.cuda.synchronize()
     idx_h = [i.cpu().numpy() for i in idxs]
     val_h = [v.cpu().numpy() for v in vals]
@@ -98,13 +114,29 @@ def test_gpt2xl_compress_and_merge_full_size():
             sub_v.append(vh[p0:p1])
         ref = oracle.merge_sparse(w0, sub_i, sub_v, wl.lr)
         np.testing.assert_array_equal(bits(w[a:b].cpu().numpy()), bits(ref), err_msg=f"merge slice [{a},{b})")
-    # untouched elements keep their bits; touched ones moved: count of changed == size of the union
+    # untouched elements keep their bits
     _progress("merge: untouched elements")
     w_ref = synth.base_weights(n, device=DEV, std=wl.w_std)
     touched = torch.zeros(n, dtype=torch.bool, device=DEV)
     for i in idxs:
         touched[i.to(torch.int64)] = True
     assert torch.equal(w[~touched].view(torch.int32), w_ref[~touched].view(torch.int32))
+    del touched
+    # the window in one call == one call per diff, over the whole array, bit for bit
+    _progress("merge: 20 single-diff calls")
+    for i, v in zip(idxs, vals):
+        ld.ld_merge_sparse(w_ref, [i], [v], wl.lr, ws_m)
+    torch.cuda.synchronize()
+    assert torch.equal(w.view(torch.int32), w_ref.view(torch.int32)), "window merge != 20 single-diff merges"
+    # and == the per-record definition redone with torch on the GPU (rounded product, then subtraction)
+    _progress("merge: per-record definition")
+    w_ref = synth.base_weights(n, device=DEV, std=wl.w_std)
+    lr_t = torch.tensor(wl.lr, dtype=torch.float32, device=DEV)
+    for i, v in zip(idxs, vals):
+        i64 = i.to(torch.int64)
+        w_ref[i64] = w_ref[i64] - lr_t * v
+        del i64
+    assert torch.equal(w.view(torch.int32), w_ref.view(torch.int32)), "window merge != per-record definition"
     del w_ref
     # --- the same window replayed through Adam on (w, m, v), checked by the oracle on the same slices
     _progress("sparse diffs through Adam")

@@ -25,21 +25,40 @@ def to_gpu(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
+def compress_paths(ws, seg_off):
+    """(path, tied flag, overflowed tiles) per segment of the last call on workspace `ws`; also checks
+    that the full-segment pass never gave up."""
+    paths, over = ld.ld_compress_topk_paths(ws, seg_off)
+    torch.cuda.synchronize()
+    paths, over = paths.cpu().numpy(), over.cpu().numpy()
+    assert not np.any(paths & 0x10000), "the full-segment pass gave up at its barrier"
+    return paths & 0xFF, (paths & 0x100) != 0, over
+
+
 def check_compress(g, r, seg_off, seg_k, select=True, tag="",
-                   strategies=(ld.LD_COMPRESS_AUTO, ld.LD_COMPRESS_FULL)):
+                   strategies=(ld.LD_COMPRESS_AUTO, ld.LD_COMPRESS_FULL), want=None):
     """Runs one compress call per strategy on the GPU and once on the oracle;
-    returns (idx, val, r_new) of the oracle."""
+    returns (idx, val, r_new) of the oracle. `want(path, tied, overflowed)` is called with what
+    the AUTO call reports about the way each segment went."""
     print(f"[compress] {tag} n={len(g)} n_seg={len(seg_k)}", flush=True)
     oi, ov, orr = oracle.topk_ef(g, r, seg_off, seg_k, select=select)
     g_gpu = to_gpu(g)
+    seg_k = np.asarray(seg_k, np.int32)
+    ws = torch.empty(max(256, ld.ld_compress_topk_workspace(seg_off, seg_k)), dtype=torch.uint8, device=DEV)
     for strategy in strategies:
         r_gpu = to_gpu(r)
-        idx, val = ld.ld_compress_topk(g_gpu, r_gpu, seg_off, seg_k, strategy=strategy)
+        idx, val = ld.ld_compress_topk(g_gpu, r_gpu, seg_off, seg_k, workspace=ws, strategy=strategy)
         torch.cuda.synchronize()
         tg = f"{tag} strategy={strategy}"
         np.testing.assert_array_equal(idx.cpu().numpy(), oi, err_msg=f"idx {tg}")
         np.testing.assert_array_equal(bits(val.cpu().numpy()), bits(ov), err_msg=f"val {tg}")
         np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(orr), err_msg=f"residual {tg}")
+        if len(seg_k) and int(np.asarray(seg_off)[-1]) > 0:
+            path, tied, over = compress_paths(ws, seg_off)
+            if strategy == ld.LD_COMPRESS_FULL:  # every segment that keeps anything went the full way
+                assert np.all(path[seg_k > 0] == ld.LD_PATH_FULL), tg
+            elif want is not None:
+                want(path, tied, over)
     return oi, ov, orr
 
 
@@ -51,7 +70,9 @@ def test_compress_flat_1m_chained():
     r = np.zeros(wl.n, np.float32)
     for t in range(3):
         g = synth.gradient(wl, t).numpy()
-        _, _, r = check_compress(g, r, off, k, select=(t > 0), tag=f"flat1m t={t}")
+        def usual(path, tied, over):
+            assert path[0] == ld.LD_PATH_CANDIDATES and not tied[0] and over[0] == 0
+        _, _, r = check_compress(g, r, off, k, select=(t > 0), tag=f"flat1m t={t}", want=usual)
 
 
 def test_compress_ragged_segments():
@@ -111,6 +132,10 @@ def test_compress_density_range(rho):
     r_gpu = to_gpu(r)
     idx, val = ld.ld_compress_topk(to_gpu(g), r_gpu, off, k, workspace=small)
     torch.cuda.synchronize()
+    path, _, over = compress_paths(small, off)
+    assert np.all(path == ld.LD_PATH_CANDIDATES)
+    if rho[0] * 100 >= 10 * rho[1]:  # 10 % and 25 %: far more candidates per tile than the minimum slot holds
+        assert over[2] > 100, "the slots were expected to overflow"
     np.testing.assert_array_equal(idx.cpu().numpy(), oi)
     np.testing.assert_array_equal(bits(val.cpu().numpy()), bits(ov))
     np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(orr))
@@ -131,18 +156,35 @@ def test_compress_massive_ties_at_the_threshold():
     lo_val = np.float32(np.abs(base[order[13_000]]))
     one = base.copy()
     one[cluster] = np.where(rs.rand(cluster.size) < 0.5, lo_val, -lo_val)
-    check_compress(one, np.zeros(n, np.float32), off, k, tag="one repeated value across the threshold")
+    # as drawn, a few other keys just below the repeated value share its fine bin: several values in an
+    # overfull bin, so the segment is redone in full
+    def redone(path, tied, over):
+        assert path[0] == ld.LD_PATH_FULL
+    check_compress(one, np.zeros(n, np.float32), off, k, tag="one repeated value and close neighbours", want=redone)
+    # with the next 300 ranks moved away the repeated value has its bin to itself: candidate path
+    def stays(path, tied, over):
+        assert path[0] == ld.LD_PATH_CANDIDATES and not tied[0]
+    alone = one.copy()
+    alone[order[13_000:13_300]] *= np.float32(0.25)
+    check_compress(alone, np.zeros(n, np.float32), off, k, tag="one repeated value across the threshold", want=stays)
+    # values on a dyadic grid (exact in fp32, so equal magnitudes are equal keys): ~7000 copies of the
+    # threshold value, more than the gather list's 4340 entries, one value per bin
+    dyadic = (np.round(base * 4096) / 4096).astype(np.float32)
+    check_compress(dyadic, np.zeros(n, np.float32), off, k, tag="dyadic grid", want=stays)
     two = one.copy()
     up = np.nextafter(lo_val, np.float32(1.0))
     two[cluster[::2]] = up
-    check_compress(two, np.zeros(n, np.float32), off, k, tag="two adjacent values across the threshold")
+    check_compress(two, np.zeros(n, np.float32), off, k, tag="two adjacent values across the threshold", want=redone)
     # frozen layer next to a live one, and values on a coarse grid (heavy duplication everywhere)
     sizes = [600_000, 400_000]
     off2 = synth.seg_offsets(sizes)
     g = base.copy()
     g[:600_000] = 0.0
     g[123] = -0.0
-    check_compress(g, np.zeros(n, np.float32), off2, synth.seg_topk(sizes, 1, 100), tag="frozen segment")
+    def frozen(path, tied, over):
+        assert path[0] == ld.LD_PATH_TIES and tied[0], "the zeros of the frozen segment: ties by index"
+        assert path[1] == ld.LD_PATH_CANDIDATES and not tied[1]
+    check_compress(g, np.zeros(n, np.float32), off2, synth.seg_topk(sizes, 1, 100), tag="frozen segment", want=frozen)
     grid = (np.round(base * 3e4) / 3e4).astype(np.float32)
     check_compress(grid, (np.round(base[::-1] * 1e4) / 3e4).astype(np.float32), off2,
                    synth.seg_topk(sizes, 1, 100), tag="values on a grid")
@@ -176,11 +218,17 @@ def test_compress_tied_segment_with_and_without_enough_ties():
     k = np.array([k_s], np.int32)
     z = np.zeros(ns, np.float32)
     few = base.copy()                                  # (b): 800 elements reach X, k is 20,000
-    check_compress(few, z, off, k, tag="tied guess, too few ties", strategies=(ld.LD_COMPRESS_AUTO,))
+    def wrong_guess(path, tied, over):
+        assert tied[0], "the sample was built to show a massively repeated key at the threshold"
+        assert path[0] == ld.LD_PATH_FULL, "too few ties: the segment must have been redone in full"
+    check_compress(few, z, off, k, tag="tied guess, too few ties", strategies=(ld.LD_COMPRESS_AUTO,), want=wrong_guess)
     many = base.copy()                                 # (a): 25,000 more copies of +-X elsewhere
     rest = np.setdiff1d(np.arange(ns), pos)
     many[rs.choice(rest, 25_000, replace=False)] = X * sign(25_000)
-    oi, ov, _ = check_compress(many, z, off, k, tag="tied guess, enough ties", strategies=(ld.LD_COMPRESS_AUTO,))
+    def right_guess(path, tied, over):
+        assert tied[0] and path[0] == ld.LD_PATH_TIES
+    oi, ov, _ = check_compress(many, z, off, k, tag="tied guess, enough ties", strategies=(ld.LD_COMPRESS_AUTO,),
+                               want=right_guess)
     assert np.count_nonzero(np.abs(ov) == X) == k_s - 200 and np.count_nonzero(np.abs(ov) > X) == 200
 
 
@@ -320,15 +368,22 @@ def test_merge_order_and_zero_diff():
     np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(w0))
 
 
+@pytest.mark.timeout(600)
 def test_compress_then_merge_end_to_end_resnet_window():
+    """Config 2 whole: ResNet-50-shaped, 161 segments, 1 %, the configuration's 50-diff window built by
+    50 chained compress calls and merged in one call; every record, residual and weight against the oracle."""
     wl = synth.workload("resnet50")
-    W = 6
+    W = wl.window
+    assert W == 50
     r_cpu = np.zeros(wl.n, np.float32)
     r_gpu = torch.zeros(wl.n, device=DEV)
+    ws = torch.empty(ld.ld_compress_topk_workspace(wl.seg_off), dtype=torch.uint8, device=DEV)
     gi, gv, oi, ov = [], [], [], []
     for t in range(W):
+        if t % 10 == 0:
+            print(f"[resnet50 window] diff {t}", flush=True)
         g = synth.gradient(wl, t).numpy()
-        a, b = ld.ld_compress_topk(to_gpu(g), r_gpu, wl.seg_off, wl.seg_k)
+        a, b = ld.ld_compress_topk(to_gpu(g), r_gpu, wl.seg_off, wl.seg_k, workspace=ws)
         gi.append(a)
         gv.append(b)
         i, v, r_cpu = oracle.topk_ef(g, r_cpu, wl.seg_off, wl.seg_k, select=True)
@@ -339,8 +394,8 @@ def test_compress_then_merge_end_to_end_resnet_window():
     ld.ld_merge_sparse(w, gi, gv, wl.lr)
     torch.cuda.synchronize()
     for t in range(W):
-        np.testing.assert_array_equal(gi[t].cpu().numpy(), oi[t])
-        np.testing.assert_array_equal(bits(gv[t].cpu().numpy()), bits(ov[t]))
+        np.testing.assert_array_equal(gi[t].cpu().numpy(), oi[t], err_msg=f"idx t={t}")
+        np.testing.assert_array_equal(bits(gv[t].cpu().numpy()), bits(ov[t]), err_msg=f"val t={t}")
     np.testing.assert_array_equal(bits(r_gpu.cpu().numpy()), bits(r_cpu))
     np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(oracle.merge_sparse(w0, oi, ov, wl.lr)))
 
@@ -877,6 +932,68 @@ def _random_case(seed):
     if rs.rand() < 0.2:
         r = (-g).astype(np.float32)
     return rs, off, np.array(ks, np.int32), g, r
+
+
+def test_configuration_model_fed_with_measured_costs():
+    # Sec. V-C closed loop, as bench.py runs it: R_B(b) and C_B(b) measured with this library (window merge
+    # fed from page-locked host memory; diffs copied out to it), handed to ld_config_select over the 24
+    # candidates of the paper's Example; every T_w and the selection must be what the oracle's Eq. (10) gives
+    # for the same measured inputs.
+    import bench
+    leg = bench.SparseLeg(synth.workload("resnet50"), torch.device(DEV), pool=4)
+    leg.step(bench.Timer())            # fills the window's 50 diffs
+    torch.cuda.synchronize()
+    row = bench.config_model_row(leg)
+    st, ms = row["stated"], row["measured_s"]
+    fs, bs = (10, 30, 50, 100), row["b_values"]
+    assert list(bs) == [1, 2, 3, 4, 5, 6]
+    tw = {}
+    for f in fs:
+        for b in bs:
+            tw[(f, b)] = oracle.wasted_time(st["N"], st["T_s"], st["M_s"], st["tau_s"], f, b, ms["R_F"], ms["R_B"][str(b)],
+                                            ms["C_F"], ms["C_B"][str(b)])
+    best = min(tw, key=tw.get)
+    assert (row["selected"]["f"], row["selected"]["b"]) == best
+    assert abs(row["selected"]["T_w_s"] - tw[best]) <= 1e-12 * tw[best]
+    for f in fs:
+        for j, b in enumerate(bs):
+            assert abs(row["T_w_normalised"][f"f={f}"][j] - tw[(f, b)] / tw[best]) <= 1e-12 * tw[(f, b)] / tw[best]
+    for b in bs:
+        want = oracle.critical_interval(st["M_s"], st["tau_s"], b, ms["R_B"][str(b)], ms["C_F"], ms["C_B"][str(b)])
+        assert abs(row["f_c"][str(b)] - want) <= 1e-12 * want
+        assert 0 < ms["C_replay"][str(b)] <= ms["R_B"][str(b)]      # replay is part of the recovery of a batch
+    assert all(ms["R_B"][str(b)] > 0 and ms["C_B"][str(b)] > 0 for b in bs) and ms["C_F"] > 0 and ms["R_F"] > 0
+
+
+def test_binding_temporaries_outlive_work_on_a_side_stream():
+    # The binding allocates a workspace itself when none is given and drops it when the call
+    # returns. With the kernels enqueued on a side stream that is still busy, torch's allocator
+    # must not hand that block to the next allocation on the default stream: the block is marked as
+    # in use on the side stream. Here the default stream grabs and zeroes same-sized blocks right
+    # after the call (an all-zero chunk table would make the merge skip every record).
+    n, W = 6_000_000, 12
+    rs = np.random.RandomState(5)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    idxs, vals = [], []
+    for t in range(W):
+        i = np.sort(rs.choice(n, n // 100, replace=False)).astype(np.int32)
+        idxs.append(i)
+        vals.append(rs.standard_normal(i.size).astype(np.float32))
+    ref = oracle.merge_sparse(w0, idxs, vals, 0.1)
+    gi, gv = [to_gpu(i) for i in idxs], [to_gpu(v) for v in vals]
+    ws_bytes = ld.ld_merge_sparse_workspace(n, [i.size for i in idxs])
+    side = torch.cuda.Stream()
+    ballast = torch.empty(1 << 28, dtype=torch.float32, device=DEV)  # 1 GiB: each fill keeps the side stream busy
+    w = to_gpu(w0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(12):
+            ballast.fill_(1.0)
+    ld.ld_merge_sparse(w, gi, gv, 0.1, stream=side, strategy=ld.LD_MERGE_SWEEP)   # workspace allocated inside
+    grabbed = [torch.zeros(ws_bytes, dtype=torch.uint8, device=DEV) for _ in range(4)]  # default stream, at once
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref))
+    del grabbed, ballast
 
 
 @pytest.mark.parametrize("block", range(4))
