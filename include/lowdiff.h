@@ -264,6 +264,34 @@ ld_status ld_merge_sparse_strategy(float* w, int64_t n,
                                    int32_t strategy);
 
 /* ------------------------------------------------------------------------
+ * ld_merge_sparse_static - ld_merge_sparse for callers that cannot allocate:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same operation, same results bit for bit, no workspace argument:
+ * the chunk table (the merge's only scratch memory) lies in a device array that
+ * is part of the library image, LD_MERGE_STATIC_SCRATCH bytes per GPU, held
+ * until the process ends.  The call allocates and frees nothing and calls no
+ * allocating routine; the first call on a device looks up that device's copy
+ * of the array (hipGetSymbolAddress), later calls only enqueue kernels.
+ *
+ *   w, n, idx, val, K, W, lr   as for ld_merge_sparse
+ * Limit: ld_merge_sparse_workspace(n, W, K) <= ld_merge_sparse_static_limit()
+ * (= LD_MERGE_STATIC_SCRATCH; a window of up to 128 diffs over about 400 M
+ * elements, or 20 diffs over the full 2^31-1); larger calls are refused with
+ * LD_ERR_WORKSPACE before anything is enqueued.
+ * Every call on a GPU shares that GPU's array: calls that overlap in time on one
+ * GPU (different streams, or threads) race on it and must be serialized by the
+ * caller.  Nothing in the array has to start at zero, and what a call leaves in
+ * it is never read by a later one.
+ * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_WORKSPACE (over the
+ * limit), LD_ERR_HIP.
+ */
+#define LD_MERGE_STATIC_SCRATCH (4u << 20)
+size_t    ld_merge_sparse_static_limit(void);
+ld_status ld_merge_sparse_static(float* w, int64_t n,
+                                 const int32_t* const* idx, const float* const* val,
+                                 const int64_t* K, int32_t W, float lr, ld_stream stream);
+
+/* ------------------------------------------------------------------------
  * ld_merge_dense_adam - replay W dense bf16 gradients through Adam onto the
  * fp32 replica (w, m, v): for s = step0+1 .. step0+W with g = widen(grad_s),
  *   m <- beta1*m + (1-beta1)*g

@@ -21,6 +21,8 @@
 //              HBM traffic: 8n + 8*sum(K) bytes + the chunk table.
 //  * scatter - one kernel per diff, one thread per record; for windows that
 //              touch only a small part of w.
+#include <atomic>
+
 #include "ld_sparse_common.h"
 
 namespace {
@@ -297,4 +299,48 @@ extern "C" ld_status ld_merge_sparse(float* w, int64_t n, const int32_t* const* 
                                      void* workspace, size_t workspace_bytes, ld_stream stream) {
     return ld_merge_sparse_strategy(w, n, idx, val, K, W, lr, workspace, workspace_bytes, stream,
                                     LD_MERGE_AUTO);
+}
+
+// ------------------------------------------------ the entry point that allocates nothing
+//
+// The chunk table is the only scratch memory of the merge. Here it lives in a file-scope
+// device array instead of a caller's workspace: one copy per GPU, held until the process
+// ends, shared by every call on that GPU. Nothing in it has to start at zero (k_chunks
+// writes every entry the sweep reads), so nothing is cleared between calls.
+static __device__ __align__(256) unsigned char scratch[LD_MERGE_STATIC_SCRATCH];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> scratch_ptr[kMaxDevices];  // per device: the address of ITS copy of `scratch`
+
+// Device address of the current device's scratch array (looked up once per device; the array's
+// name is only a host-side handle and is never passed to a kernel).
+ld_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LD_ERR_HIP;
+    void* p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LD_ERR_HIP;
+        scratch_ptr[dev].store(p, std::memory_order_release);  // every thread finds the same address
+    }
+    *out = p;
+    return LD_OK;
+}
+
+}  // namespace
+
+extern "C" size_t ld_merge_sparse_static_limit(void) { return LD_MERGE_STATIC_SCRATCH; }
+
+extern "C" ld_status ld_merge_sparse_static(float* w, int64_t n, const int32_t* const* idx,
+                                            const float* const* val, const int64_t* K, int32_t W, float lr,
+                                            ld_stream stream) {
+    const ld_status st = check_diff_args(w, n, idx, val, K, W);
+    if (st != LD_OK) return st;
+    if (ld_merge_sparse_workspace(n, W, K) > LD_MERGE_STATIC_SCRATCH) return LD_ERR_WORKSPACE;
+    if (W == 0 || n == 0) return LD_OK;
+    void* ptr = nullptr;
+    const ld_status sp = static_scratch(&ptr);
+    if (sp != LD_OK) return sp;
+    return merge_sparse_impl(w, n, idx, val, K, W, lr, ptr, LD_MERGE_STATIC_SCRATCH, stream, LD_MERGE_AUTO);
 }

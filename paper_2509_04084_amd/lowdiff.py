@@ -72,6 +72,10 @@ def load() -> ctypes.CDLL:
     lib.ld_merge_sparse.restype = i32
     lib.ld_merge_sparse_strategy.argtypes = [vp, i64, vp, vp, vp, i32, f32, vp, sz, vp, i32]
     lib.ld_merge_sparse_strategy.restype = i32
+    lib.ld_merge_sparse_static_limit.argtypes = []
+    lib.ld_merge_sparse_static_limit.restype = sz
+    lib.ld_merge_sparse_static.argtypes = [vp, i64, vp, vp, vp, i32, f32, vp]
+    lib.ld_merge_sparse_static.restype = i32
     lib.ld_merge_dense_adam.argtypes = [vp, vp, vp, i64, vp, i32, i64, f32, f32, f32, f32, vp]
     lib.ld_merge_dense_adam.restype = i32
     lib.ld_merge_sparse_adam_workspace.argtypes = [i64, i32, vp]
@@ -268,6 +272,28 @@ def ld_merge_sparse(w: torch.Tensor, idx: Sequence[torch.Tensor], val: Sequence[
                                       ctypes.c_float(lr), _dev(workspace, torch.uint8, "workspace"),
                                       workspace.numel(), _stream(stream), int(strategy))
     _check("ld_merge_sparse", st)
+
+
+def ld_merge_sparse_static_limit() -> int:
+    return int(load().ld_merge_sparse_static_limit())
+
+
+def ld_merge_sparse_static(w: torch.Tensor, idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], lr: float,
+                           stream=None) -> None:
+    """ld_merge_sparse without a workspace and without any allocation (the chunk table lies in a
+    device array of the library); refuses windows beyond ld_merge_sparse_static_limit()."""
+    W = len(idx)
+    if len(val) != W:
+        raise ValueError("idx and val differ in length")
+    K = np.array([t.numel() for t in idx], dtype=np.int64)
+    for a, b in zip(idx, val):
+        if a.numel() != b.numel():
+            raise ValueError("idx[t] and val[t] differ in size")
+    ip = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.int32, "idx").value or 0 for t in idx])
+    vp = (ctypes.c_void_p * max(W, 1))(*[_dev(t, torch.float32, "val").value or 0 for t in val])
+    st = load().ld_merge_sparse_static(_dev(w, torch.float32, "w"), w.numel(), ip, vp, _hp(K), W,
+                                       ctypes.c_float(lr), _stream(stream))
+    _check("ld_merge_sparse_static", st)
 
 
 def ld_merge_dense_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grads_bf16: Sequence[torch.Tensor],

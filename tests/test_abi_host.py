@@ -267,6 +267,23 @@ def test_binding_refuses_mismatched_sizes_and_devices_before_any_launch():
         ld.ld_merge_sparse(w, [i], [torch.zeros(4, device="meta")], 0.1)
 
 
+def test_static_merge_refuses_on_the_host():
+    lib = ld.load()
+    assert lib.ld_merge_sparse_static_limit() == 4 << 20
+    V = ctypes.c_void_p
+    W = 128
+    K = np.full(W, 4, np.int64)
+    ip = (ctypes.c_void_p * W)(*[FAKE] * W)
+    n_big = 2 ** 31 - 1
+    assert ld.ld_merge_sparse_workspace(n_big, K) > 4 << 20
+    call = lambda w, n, W_: lib.ld_merge_sparse_static(V(w), n, ip, ip, _p(K), W_, ctypes.c_float(0.1), V(0))
+    assert call(FAKE, n_big, W) == -3          # chunk table beyond the library's scratch array
+    assert call(0, 1024, 1) == -1
+    assert call(FAKE, 2 ** 31, 1) == -2
+    assert call(FAKE + 4, 1024, 1) == -5
+    assert call(FAKE, 1024, 0) == 0            # empty window: nothing to do, nothing looked up
+
+
 def test_compress_paths_argument_errors():
     lib = ld.load()
     V = ctypes.c_void_p
