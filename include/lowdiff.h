@@ -215,7 +215,18 @@ ld_status ld_merge_sparse(float* w, int64_t n,
  *   workspace  dev, 256-byte aligned, ld_merge_sparse_workspace(n, group, K) bytes
  *   copy_stream, merge_stream  may be the same stream (then nothing overlaps).
  *              w is ready when merge_stream has passed the call.
- * The call creates and destroys four HIP events; it allocates no memory.
+ * The call creates and destroys four HIP events (it allocates no device memory), so
+ * it cannot be recorded into a HIP graph; ld_merge_sparse_from_host_events takes the
+ * four events from the caller instead and then only enqueues copies, kernels, event
+ * records and stream waits:
+ *   events     host array of 4 hipEvent_t the caller created (timing may be disabled)
+ *              and does not use for anything else while the call's work is pending;
+ *              NULL: as ld_merge_sparse_from_host
+ * Unlike the other entry points, this one can fail part-way: argument errors are
+ * found before anything is enqueued, but when a HIP call fails in the loop over the
+ * groups (LD_ERR_HIP) the earlier groups have been enqueued and will be merged into
+ * w; w then holds base + the first whole groups and must be rebuilt from the base
+ * checkpoint.
  * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_WORKSPACE, LD_ERR_HIP.
  */
 size_t    ld_merge_sparse_from_host_staging(const int64_t* K /* host */, int32_t W, int32_t group);
@@ -225,6 +236,13 @@ ld_status ld_merge_sparse_from_host(float* w, int64_t n,
                                     void* staging, size_t staging_bytes,
                                     void* workspace, size_t workspace_bytes,
                                     ld_stream copy_stream, ld_stream merge_stream);
+ld_status ld_merge_sparse_from_host_events(float* w, int64_t n,
+                                           const int32_t* const* host_idx, const float* const* host_val,
+                                           const int64_t* K, int32_t W, float lr, int32_t group,
+                                           void* staging, size_t staging_bytes,
+                                           void* workspace, size_t workspace_bytes,
+                                           ld_stream copy_stream, ld_stream merge_stream,
+                                           void* const* events /* host, 4 hipEvent_t, or NULL */);
 
 /* ------------------------------------------------------------------------
  * ld_check_diff - does a differential that was read back from storage meet

@@ -31,7 +31,11 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lowdiff_oracle.cpp")
-_LIB = os.path.join(_HERE, "liblowdiff_oracle.so")
+# LOWDIFF_ORACLE_SANITIZE=1 selects a second build of the same source with AddressSanitizer and
+# UndefinedBehaviorSanitizer (host code only); the process must then have been started with the
+# sanitizer runtime preloaded (tests/test_oracle_sanitized.py does that in a child process).
+SANITIZED = os.environ.get("LOWDIFF_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "liblowdiff_oracle_san.so" if SANITIZED else "liblowdiff_oracle.so")
 _lib = None
 
 
@@ -39,8 +43,9 @@ def build(force: bool = False) -> str:
     """Compile the oracle with the host compiler; returns the library path."""
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
-        cmd = ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fPIC", "-shared",
-               "-o", _LIB + ".tmp", _SRC]
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+               "-fno-omit-frame-pointer"] if SANITIZED else ["-O2"]
+        cmd = ["g++"] + opt + ["-std=c++17", "-ffp-contract=off", "-fPIC", "-shared", "-o", _LIB + ".tmp", _SRC]
         subprocess.run(cmd, check=True)
         os.replace(_LIB + ".tmp", _LIB)
     return _LIB

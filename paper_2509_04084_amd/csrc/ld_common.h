@@ -56,6 +56,9 @@ static inline void ld_fill_adam_steps(LdAdamSteps& a, int32_t W, int64_t step0, 
     a.eps = eps;
 }
 
+// Whether a replay with this eps needs the square root that handles denormal arguments.
+static inline bool ld_adam_careful(float eps) { return !(eps >= 1e-12f); }
+
 #ifdef __HIPCC__
 
 typedef float ld_f32x4 __attribute__((ext_vector_type(4)));
@@ -112,12 +115,27 @@ __device__ __forceinline__ float ld_bf16_widen(uint32_t h) { return __uint_as_fl
 // corrected second moment). The only place the arithmetic is written: every replay
 // kernel, fused window or single step, dense or sparse gradient, runs these operations.
 //   lr_bc1 = lr / (1 - beta1^s), ibc2 = 1 / (1 - beta2^s), both prepared on the host in double
+// The hardware square root takes a denormal argument for zero. Next to an eps of ordinary size
+// that is far below the tolerance (the root of a denormal is below 1.1e-19); with eps = 0, or an eps
+// that small, it would decide the result (a zero denominator). TINY_EPS (chosen per call from eps,
+// see ld_adam_careful) scales such arguments into the normal range first: sqrt(x) =
+// sqrt(x * 2^64) * 2^-32, exact scalings.
+template <bool TINY_EPS>
 __device__ __forceinline__ void ld_adam_step(float& w, float& m, float& v, float g, float b1,
                                              float omb1, float b2, float omb2, float eps,
                                              float lr_bc1, float ibc2) {
     m = __fmaf_rn(b1, m, __fmul_rn(omb1, g));
     v = __fmaf_rn(b2, v, __fmul_rn(__fmul_rn(omb2, g), g));
-    const float denom = __fadd_rn(__builtin_amdgcn_sqrtf(__fmul_rn(v, ibc2)), eps);
+    float x = __fmul_rn(v, ibc2), root;
+    if (TINY_EPS) {
+        const bool tiny = x < 0x1p-96f;
+        x = tiny ? __fmul_rn(x, 0x1p+64f) : x;
+        root = __builtin_amdgcn_sqrtf(x);
+        root = tiny ? __fmul_rn(root, 0x1p-32f) : root;
+    } else {
+        root = __builtin_amdgcn_sqrtf(x);
+    }
+    const float denom = __fadd_rn(root, eps);
     const float upd = __fmul_rn(__fmul_rn(lr_bc1, m), __builtin_amdgcn_rcpf(denom));
     w = __fsub_rn(w, upd);
 }

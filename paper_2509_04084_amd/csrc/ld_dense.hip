@@ -99,7 +99,7 @@ typedef uint32_t ld_u32x2 __attribute__((ext_vector_type(2)));
 // lane), and all loads are issued before the first value is used. Consecutive
 // workgroups go to different XCDs, so each XCD is given one contiguous eighth of
 // the arrays (its address translations and DRAM pages stay its own).
-template <int WT>
+template <int WT, bool TINY_EPS>
 __global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, float* __restrict__ m,
                                                        float* __restrict__ v, int64_t n, AdamArgs a, int t0) {
     const int64_t per = (static_cast<int64_t>(gridDim.x) + 7) / 8;
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, fl
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const uint32_t half = (e & 1) ? (gw[e >> 1] >> 16) : (gw[e >> 1] & 0xFFFFu);
-                        ld_adam_step(ww[e], mm[e], v4_[e], ld_bf16_widen(half), a.s.beta1, a.s.one_m_beta1, a.s.beta2,
+                        ld_adam_step<TINY_EPS>(ww[e], mm[e], v4_[e], ld_bf16_widen(half), a.s.beta1, a.s.one_m_beta1, a.s.beta2,
                                   a.s.one_m_beta2, a.s.eps, lr_bc1, ibc2);
                     }
                 }
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kAdamThreads) void k_adam(float* __restrict__ w, fl
         for (int64_t e = b0 + threadIdx.x; e < n; e += kAdamThreads) {
             float ww = w[e], mm = m[e], v1 = v[e];
             for (int t = t0; t < t0 + WT && t < a.W; ++t)
-                ld_adam_step(ww, mm, v1, ld_bf16_widen(a.grad[t][e]), a.s.beta1, a.s.one_m_beta1, a.s.beta2,
+                ld_adam_step<TINY_EPS>(ww, mm, v1, ld_bf16_widen(a.grad[t][e]), a.s.beta1, a.s.one_m_beta1, a.s.beta2,
                           a.s.one_m_beta2, a.s.eps, a.s.lr_over_bc1[t], a.s.inv_bc2[t]);
             w[e] = ww;
             m[e] = mm;
@@ -247,13 +247,21 @@ extern "C" ld_status ld_merge_dense_adam(float* w, float* m, float* v, int64_t n
     ld_begin_call();
     // steps are fused four (or eight) at a time; the state round-trips through fp32
     // memory between passes, which is exactly what it does between two calls
+    const bool careful = ld_adam_careful(eps);
     int t0 = 0;
     while (t0 < W) {
         const int left = W - t0;
-        if (left > 4) { k_adam<8><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 8; }
-        else if (left > 2) { k_adam<4><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 4; }
-        else if (left > 1) { k_adam<2><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 2; }
-        else { k_adam<1><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 1; }
+        if (careful) {
+            if (left > 4) { k_adam<8, true><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 8; }
+            else if (left > 2) { k_adam<4, true><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 4; }
+            else if (left > 1) { k_adam<2, true><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 2; }
+            else { k_adam<1, true><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 1; }
+        } else {
+            if (left > 4) { k_adam<8, false><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 8; }
+            else if (left > 2) { k_adam<4, false><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 4; }
+            else if (left > 1) { k_adam<2, false><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 2; }
+            else { k_adam<1, false><<<grid, block, 0, s>>>(w, m, v, n, a, t0); t0 += 1; }
+        }
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     }
     return LD_OK;

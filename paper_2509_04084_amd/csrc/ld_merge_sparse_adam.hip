@@ -40,6 +40,7 @@ __device__ __forceinline__ void scatter_from(float* tile, const int32_t* __restr
     }
 }
 
+template <bool TINY_EPS>
 __global__ __launch_bounds__(LD_WAVE) void k_sparse_adam(float* __restrict__ w, float* __restrict__ m,
                                                          float* __restrict__ v, int64_t n, int32_t nchunk,
                                                          DiffTable tb, int32_t W, LdAdamSteps a,
@@ -154,7 +155,7 @@ __global__ __launch_bounds__(LD_WAVE) void k_sparse_adam(float* __restrict__ w, 
                     const float gq[4] = {g4.x, g4.y, g4.z, g4.w};
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
-                        ld_adam_step(ww[j][q], mm[j][q], vv[j][q], gq[q], a.beta1, a.one_m_beta1, a.beta2,
+                        ld_adam_step<TINY_EPS>(ww[j][q], mm[j][q], vv[j][q], gq[q], a.beta1, a.one_m_beta1, a.beta2,
                                      a.one_m_beta2, a.eps, lr_bc1, ibc2);
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -225,7 +226,10 @@ extern "C" ld_status ld_merge_sparse_adam(float* w, float* m, float* v, int64_t 
         ld_fill_adam_steps(a, gw, step0 + g0, lr, beta1, beta2, eps);
         launch_chunks(tb, gw, n, nchunk, ctab, s);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
-        k_sparse_adam<<<dim3((nsub + 7) / 8 * 8), dim3(LD_WAVE), 0, s>>>(w, m, v, n, nchunk, tb, gw, a, ctab);
+        if (ld_adam_careful(eps))
+            k_sparse_adam<true><<<dim3((nsub + 7) / 8 * 8), dim3(LD_WAVE), 0, s>>>(w, m, v, n, nchunk, tb, gw, a, ctab);
+        else
+            k_sparse_adam<false><<<dim3((nsub + 7) / 8 * 8), dim3(LD_WAVE), 0, s>>>(w, m, v, n, nchunk, tb, gw, a, ctab);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     }
     return LD_OK;

@@ -32,7 +32,18 @@ size_t slot_bytes(const int64_t* K, int32_t W, int32_t group) {
 
 struct Events {
     hipEvent_t copied[kSlots] = {nullptr, nullptr}, merged[kSlots] = {nullptr, nullptr};
-    bool create() {
+    bool owned = false;
+    // The caller's four events (copied[0], copied[1], merged[0], merged[1]), or events of the call's own.
+    bool init(void* const* given) {
+        if (given) {
+            for (int i = 0; i < kSlots; ++i) {
+                copied[i] = static_cast<hipEvent_t>(given[i]);
+                merged[i] = static_cast<hipEvent_t>(given[kSlots + i]);
+                if (!copied[i] || !merged[i]) return false;
+            }
+            return true;
+        }
+        owned = true;
         for (int i = 0; i < kSlots; ++i) {
             if (hipEventCreateWithFlags(&copied[i], hipEventDisableTiming) != hipSuccess) return false;
             if (hipEventCreateWithFlags(&merged[i], hipEventDisableTiming) != hipSuccess) return false;
@@ -40,6 +51,7 @@ struct Events {
         return true;
     }
     ~Events() {  // an event that is still pending is released when it completes
+        if (!owned) return;
         for (int i = 0; i < kSlots; ++i) {
             if (copied[i]) (void)hipEventDestroy(copied[i]);
             if (merged[i]) (void)hipEventDestroy(merged[i]);
@@ -56,11 +68,12 @@ extern "C" size_t ld_merge_sparse_from_host_staging(const int64_t* K, int32_t W,
     return kSlots * slot_bytes(K, W, group < W ? group : W);
 }
 
-extern "C" ld_status ld_merge_sparse_from_host(float* w, int64_t n, const int32_t* const* host_idx,
-                                               const float* const* host_val, const int64_t* K, int32_t W,
-                                               float lr, int32_t group, void* staging, size_t staging_bytes,
-                                               void* workspace, size_t workspace_bytes, ld_stream copy_stream,
-                                               ld_stream merge_stream) {
+extern "C" ld_status ld_merge_sparse_from_host_events(float* w, int64_t n, const int32_t* const* host_idx,
+                                                      const float* const* host_val, const int64_t* K, int32_t W,
+                                                      float lr, int32_t group, void* staging, size_t staging_bytes,
+                                                      void* workspace, size_t workspace_bytes,
+                                                      ld_stream copy_stream, ld_stream merge_stream,
+                                                      void* const* events) {
     if (n < 0 || n > INT32_MAX || W < 0 || W > LD_MAX_WINDOW || group <= 0 || group > kGroupLimit)
         return LD_ERR_RANGE;
     if (W == 0 || n == 0) return LD_OK;
@@ -77,7 +90,7 @@ extern "C" ld_status ld_merge_sparse_from_host(float* w, int64_t n, const int32_
         return LD_ERR_WORKSPACE;
     hipStream_t cs = static_cast<hipStream_t>(copy_stream), ms = static_cast<hipStream_t>(merge_stream);
     Events ev;
-    if (!ev.create()) return LD_ERR_HIP;
+    if (!ev.init(events)) return events ? LD_ERR_NULL : LD_ERR_HIP;
 
     int32_t stage = 0;
     for (int32_t g0 = 0; g0 < W; g0 += group, ++stage) {
@@ -110,4 +123,13 @@ extern "C" ld_status ld_merge_sparse_from_host(float* w, int64_t n, const int32_
         LD_HIP_OK(hipEventRecord(ev.merged[s], ms));
     }
     return LD_OK;
+}
+
+extern "C" ld_status ld_merge_sparse_from_host(float* w, int64_t n, const int32_t* const* host_idx,
+                                               const float* const* host_val, const int64_t* K, int32_t W,
+                                               float lr, int32_t group, void* staging, size_t staging_bytes,
+                                               void* workspace, size_t workspace_bytes, ld_stream copy_stream,
+                                               ld_stream merge_stream) {
+    return ld_merge_sparse_from_host_events(w, n, host_idx, host_val, K, W, lr, group, staging, staging_bytes,
+                                            workspace, workspace_bytes, copy_stream, merge_stream, nullptr);
 }

@@ -52,6 +52,8 @@ def load() -> ctypes.CDLL:
     lib.ld_merge_sparse_from_host_staging.restype = sz
     lib.ld_merge_sparse_from_host.argtypes = [vp, i64, vp, vp, vp, i32, f32, i32, vp, sz, vp, sz, vp, vp]
     lib.ld_merge_sparse_from_host.restype = i32
+    lib.ld_merge_sparse_from_host_events.argtypes = [vp, i64, vp, vp, vp, i32, f32, i32, vp, sz, vp, sz, vp, vp, vp]
+    lib.ld_merge_sparse_from_host_events.restype = i32
     lib.ld_check_diff.argtypes = [vp, vp, i64, i64, vp, vp]
     lib.ld_check_diff.restype = i32
     lib.ld_compress_topk_workspace_for.argtypes = [i32, vp, vp]
@@ -317,10 +319,11 @@ def ld_merge_dense_adam(w: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grads
 def ld_merge_sparse_from_host(w: torch.Tensor, idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], lr: float,
                               group: int = 4, staging: Optional[torch.Tensor] = None,
                               workspace: Optional[torch.Tensor] = None, copy_stream=None,
-                              merge_stream=None) -> None:
+                              merge_stream=None, events: Optional[Sequence[int]] = None) -> None:
     """ld_merge_sparse for diffs in (pinned) host tensors: groups of `group` diffs are copied on
     `copy_stream` while the previous group is merged on `merge_stream` (default: the current stream
-    for both, i.e. no overlap). The host tensors must stay alive until the copies are done."""
+    for both, i.e. no overlap). The host tensors must stay alive until the copies are done.
+    `events`: four hipEvent_t handles of the caller's (then the call creates none of its own)."""
     lib = load()
     W = len(idx)
     if len(val) != W:
@@ -340,10 +343,15 @@ def ld_merge_sparse_from_host(w: torch.Tensor, idx: Sequence[torch.Tensor], val:
                              w.device, copy_stream, merge_stream)
     ip = (ctypes.c_void_p * max(W, 1))(*[t.data_ptr() for t in idx])
     vp = (ctypes.c_void_p * max(W, 1))(*[t.data_ptr() for t in val])
-    st = lib.ld_merge_sparse_from_host(_dev(w, torch.float32, "w"), n, ip, vp, _hp(K), W, ctypes.c_float(lr), group,
-                                       _dev(staging, torch.uint8, "staging"), staging.numel(),
-                                       _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
-                                       _stream(copy_stream), _stream(merge_stream))
+    ev = None
+    if events is not None:
+        if len(events) != 4:
+            raise ValueError("events: four hipEvent_t handles expected")
+        ev = (ctypes.c_void_p * 4)(*[int(e) for e in events])
+    st = lib.ld_merge_sparse_from_host_events(_dev(w, torch.float32, "w"), n, ip, vp, _hp(K), W, ctypes.c_float(lr),
+                                              group, _dev(staging, torch.uint8, "staging"), staging.numel(),
+                                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                              _stream(copy_stream), _stream(merge_stream), ev)
     _check("ld_merge_sparse_from_host", st)
 
 

@@ -468,6 +468,47 @@ def test_adam_replay_parity(n, W, step0):
         assert torch.equal(a.view(torch.int32), b.view(torch.int32))
 
 
+@pytest.mark.parametrize("eps", [0.0, 1e-20])
+def test_adam_with_no_eps_and_denormal_second_moments(eps):
+    # With eps = 0 (or far below the root of a denormal) the denominator is sqrt(v / bc2) alone, and for
+    # gradients below 1e-19 that argument is a denormal fp32 number: a square root that takes denormals
+    # for zero would divide by zero. Gradients from 1e-3 down to 3e-20, no zeros (0 / 0 has no value to
+    # compare); dense replay and sparse replay of the same gradients.
+    n, W = 40_003, 3
+    rs = np.random.RandomState(71)
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    z = np.zeros(n, np.float32)
+    grads = []
+    for _ in range(W):
+        mag = 10.0 ** rs.uniform(-19.5, -3.0, n)
+        g = (mag * np.where(rs.rand(n) < 0.5, 1.0, -1.0)).astype(np.float32)
+        grads.append(to_gpu(g).to(torch.bfloat16))
+    assert all(bool((g.float().abs() > 1e-20).all()) for g in grads)
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=eps)
+    gb = [_bf16_bits_t(g) for g in grads]
+    ref = oracle.adam_replay(w0, z, z, gb, 0, **hp)
+    assert np.all(np.isfinite(ref[0]))
+    assert int((grads[0].float().abs() < 1.0e-19).sum()) > 500   # first step: v / bc2 = g^2 is a denormal for these
+    w, m, v = to_gpu(w0), to_gpu(z), to_gpu(z)
+    ld.ld_merge_dense_adam(w, m, v, grads, 0, **hp)
+    # the same gradients as sparse diffs that record every position
+    ws, ms_, vs = to_gpu(w0), to_gpu(z), to_gpu(z)
+    allpos = torch.arange(n, dtype=torch.int32, device=DEV)
+    ld.ld_merge_sparse_adam(ws, ms_, vs, [allpos] * W, [g.float() for g in grads], 0, **hp)
+    torch.cuda.synchronize()
+    for got in ((w, m, v), (ws, ms_, vs)):
+        for name, a, b in zip("wmv", got, ref):
+            a = a.cpu().numpy().astype(np.float64)
+            err = np.abs(a - b.astype(np.float64))
+            assert np.all(err <= 1e-7 + 1e-6 * np.abs(b)), f"eps={eps} {name}: max err {err.max()}"
+        a, b = got[2].cpu().numpy().astype(np.float64), ref[2].astype(np.float64)
+        normal = b >= 1.1755e-38   # a denormal v has few bits: the relative bound is for the normal ones
+        assert np.all(np.abs(a - b)[normal] <= 1e-6 * b[normal])
+        assert np.all(np.abs(a - b)[~normal] <= 3e-45)   # and at most two steps of the denormal grid elsewhere
+    for a, b in ((w, ws), (m, ms_), (v, vs)):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
 def test_adam_zero_gradient_and_closed_form():
     n = 4096
     hp = dict(lr=1e-2, **synth.ADAM)
@@ -691,6 +732,23 @@ def test_merge_from_pinned_host_equals_the_window_merge(group):
         ld.ld_merge_sparse_from_host(w2, hi, hv, 0.1, group=group, staging=staging)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(bits(w2.cpu().numpy()), bits(ref))
+    # with four events of the caller's the call creates none of its own; the same events serve call after call
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    events = []
+    for _ in range(4):
+        e = ctypes.c_void_p()
+        assert hip.hipEventCreateWithFlags(ctypes.byref(e), 2) == 0     # hipEventDisableTiming
+        events.append(e.value)
+    for _ in range(2):
+        w3 = to_gpu(w0)
+        torch.cuda.synchronize()
+        ld.ld_merge_sparse_from_host(w3, hi, hv, 0.1, group=group, copy_stream=copy_s, merge_stream=merge_s, events=events)
+        merge_s.synchronize()
+        copy_s.synchronize()
+        np.testing.assert_array_equal(bits(w3.cpu().numpy()), bits(ref))
+    for e in events:
+        assert hip.hipEventDestroy(ctypes.c_void_p(e)) == 0
 
 
 # ------------------------------------------------- workspaces hold anything on entry
