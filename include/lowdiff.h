@@ -188,10 +188,14 @@ ld_status ld_snapshot_layers(const void* const* src, void* const* dst, const int
  *              ascending and in [0, n); val[t] fp32[K[t]]
  *   K          host [W] int64, 0 <= K[t] <= n
  *   W          0 <= W <= LD_MAX_WINDOW (0 enqueues nothing)
- *   workspace  dev, 256-byte aligned, ld_merge_sparse_workspace() bytes
+ *   workspace  dev, 256-byte aligned, ld_merge_sparse_workspace() bytes. With K = NULL
+ *              the query gives the minimum (the call fails with less); with K it
+ *              gives what the window's shape asks for, which is more for long windows
+ *              of very sparse diffs (they then run a lane per diff instead of as
+ *              ordinary sweeps; same result, less time)
  * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_WORKSPACE, LD_ERR_HIP.
  */
-size_t    ld_merge_sparse_workspace(int64_t n, int32_t W, const int64_t* K /* host */);
+size_t    ld_merge_sparse_workspace(int64_t n, int32_t W, const int64_t* K /* host, or NULL */);
 ld_status ld_merge_sparse(float* w, int64_t n,
                           const int32_t* const* idx, const float* const* val,
                           const int64_t* K, int32_t W, float lr,
@@ -292,7 +296,7 @@ ld_status ld_merge_sparse_strategy(float* w, int64_t n,
  * of the array (hipGetSymbolAddress), later calls only enqueue kernels.
  *
  *   w, n, idx, val, K, W, lr   as for ld_merge_sparse
- * Limit: ld_merge_sparse_workspace(n, W, K) <= ld_merge_sparse_static_limit()
+ * Limit: ld_merge_sparse_workspace(n, W, NULL) <= ld_merge_sparse_static_limit()
  * (= LD_MERGE_STATIC_SCRATCH; a window of up to 128 diffs over about 400 M
  * elements, or 20 diffs over the full 2^31-1); larger calls are refused with
  * LD_ERR_WORKSPACE before anything is enqueued.

@@ -200,6 +200,280 @@ __global__ __launch_bounds__(LD_WAVE) void k_merge_sweep(float* __restrict__ w, 
     }
 }
 
+// ------------------------------------------------------- thin long windows: a lane per diff
+//
+// A long window of very sparse diffs (config 3: 100 diffs of 0.1 %, eight records per diff and
+// sub-tile) leaves the sweep above with a wave's 64 lanes serving eight records at a time, a
+// hundred times in a row. Here the roles are turned round: lane t holds ALL the records of diff t
+// (and t + 64) that fall into the wave's sub-tile and the diffs are applied side by side. Where
+// exactly a diff's records for a sub-tile begin comes from a table of its own (k_subtab: one
+// streaming pass over the index arrays, which are small when diffs are this sparse).
+//
+// Order: an element that only one diff of the window touches can be updated at any time. Elements
+// touched by several diffs are found first (two bitmaps in LDS: seen, seen again) and their
+// records are held back; these are then applied in rounds: every pending record bids for its
+// element's slot of a small owner table with (diff, element) as the key, the smallest key wins the
+// slot (atomic minimum), applies its update and leaves; so the updates of one element go through
+// in diff order whatever else shares the slot.
+#ifndef LD_THIN_SUB
+#define LD_THIN_SUB 4096
+#endif
+#ifndef LD_THIN_CAP
+#define LD_THIN_CAP 24
+#endif
+#ifndef LD_THIN_OWNER
+#define LD_THIN_OWNER 128
+#endif
+constexpr int kThinSub = LD_THIN_SUB;    // elements of a wave's sub-tile in this kernel
+constexpr int kThinCap = LD_THIN_CAP;    // records of one diff in one sub-tile that a lane can hold
+constexpr int kThinSlots = (kThinCap + 3 + 3) / 4 * 4;  // register slots: the records come in aligned blocks of four
+constexpr int kConfLane = 4;             // held-back records a lane can keep
+constexpr int kBitWords = kThinSub / 32;
+constexpr int kOwner = LD_THIN_OWNER;    // slots of the owner table
+static_assert(kThinSub % (4 * LD_WAVE) == 0 && kThinSub % 32 == 0 && kThinSub <= 8192, "whole rows of 16-byte accesses; 13 bits of element in a key");
+
+// tab[t * (nsub + 1) + s] = number of records of diff t with idx < s * kThinSub, s = 0 .. nsub.
+// A thread looks at four consecutive records (one 16-byte load; the arrays of this path are
+// 16-byte aligned) and at the one before them, and fills the entries between the sub-tiles of
+// neighbouring records; the thread that meets record K closes the row.
+constexpr int kSubtabPer = 4;
+
+__global__ __launch_bounds__(256) void k_subtab(DiffTable tb, int32_t nsub, int32_t* __restrict__ tab) {
+    const int t = blockIdx.y;
+    const int32_t K = tb.K[t];
+    const int32_t* __restrict__ idx = tb.idx[t];
+    const int32_t j0 = (static_cast<int32_t>(blockIdx.x) * 256 + static_cast<int32_t>(threadIdx.x)) * kSubtabPer;
+    if (j0 > K) return;
+    // the block of four that holds record j0 lies inside the array's last 16 bytes at worst
+    ld_u32x4 q = {0u, 0u, 0u, 0u};
+    if (j0 < K) q = *reinterpret_cast<const ld_u32x4*>(idx + j0);
+    const int32_t v[kSubtabPer] = {static_cast<int32_t>(q.x), static_cast<int32_t>(q.y), static_cast<int32_t>(q.z),
+                                   static_cast<int32_t>(q.w)};
+    int32_t a = j0 == 0 ? -1 : idx[j0 - 1] / kThinSub;
+    int32_t* row = tab + static_cast<int64_t>(t) * (nsub + 1);
+#pragma unroll
+    for (int c = 0; c < kSubtabPer; ++c) {
+        const int32_t j = j0 + c;
+        if (j > K) break;
+        int32_t b = j == K ? nsub : v[c] / kThinSub;
+        if (a >= nsub) a = nsub - 1;   // an index outside [0, n) breaks the caller's contract: stay inside the row
+        if (a < -1) a = -1;
+        if (b > nsub) b = nsub;
+        for (int32_t s = a + 1; s <= b; ++s) row[s] = j;
+        a = b;
+    }
+}
+
+__device__ __forceinline__ int32_t wave_max(int32_t x) {
+#pragma unroll
+    for (int d = LD_WAVE / 2; d > 0; d >>= 1) {
+        const int32_t y = __shfl_xor(x, d, LD_WAVE);
+        x = y > x ? y : x;
+    }
+    return x;
+}
+
+template <int SETS>
+__global__ __launch_bounds__(LD_WAVE) void k_merge_thin(float* __restrict__ w, int64_t n, int32_t nsub,
+                                                        DiffTable tb, int32_t W, const int32_t* __restrict__ tab,
+                                                        float lr) {
+    __shared__ float tile[kThinSub];
+    __shared__ uint32_t seen[kBitWords], multi[kBitWords];
+    __shared__ uint32_t owner[kOwner];
+    const int lane = threadIdx.x;
+    const int64_t per = (static_cast<int64_t>(gridDim.x) + 7) / 8;   // each XCD walks one contiguous eighth of w
+    const int64_t sub = static_cast<int64_t>(blockIdx.x % 8) * per + blockIdx.x / 8;
+    if (sub * kThinSub >= n) return;
+    const int64_t lo64 = sub * kThinSub;
+    const int32_t len = static_cast<int32_t>((n - lo64) < kThinSub ? (n - lo64) : kThinSub);
+    const int32_t lo = static_cast<int32_t>(lo64);
+    const bool full = (len == kThinSub);
+
+    ld_f32x4 x[kThinSub / 4 / LD_WAVE];
+    if (full) {
+        const ld_f32x4* src = reinterpret_cast<const ld_f32x4*>(w + lo64);
+#pragma unroll
+        for (int j = 0; j < kThinSub / 4 / LD_WAVE; ++j) x[j] = ld_nt_load(src + j * LD_WAVE + lane);
+    }
+    // lane t: the records of diffs t (and t + 64) inside this sub-tile
+    int32_t p0[SETS], cnt[SETS];
+    const int32_t* ip[SETS];
+    const float* vp[SETS];
+    int32_t most = 0, slots = 0;
+#pragma unroll
+    for (int h = 0; h < SETS; ++h) {
+        const int t = h * LD_WAVE + lane;
+        p0[h] = cnt[h] = 0;
+        ip[h] = nullptr;
+        vp[h] = nullptr;
+        if (t < W) {
+            const int32_t* row = tab + static_cast<int64_t>(t) * (nsub + 1) + sub;
+            p0[h] = row[0];
+            cnt[h] = row[1] - p0[h];
+            ip[h] = tb.idx[t];
+            vp[h] = tb.val[t];
+        }
+        most = cnt[h] > most ? cnt[h] : most;
+        const int32_t used = (p0[h] & 3) + cnt[h];   // slots of 16-byte blocks the lane's records reach into
+        slots = used > slots ? used : slots;
+    }
+    most = wave_max(most);
+    slots = wave_max(slots);
+    if (full) {
+#pragma unroll
+        for (int j = 0; j < kThinSub / 4 / LD_WAVE; ++j) reinterpret_cast<ld_f32x4*>(tile)[j * LD_WAVE + lane] = x[j];
+    } else {
+        for (int32_t e = lane; e < len; e += LD_WAVE) tile[e] = w[lo64 + e];
+    }
+    for (int q = lane; q < kOwner; q += LD_WAVE) owner[q] = 0xFFFFFFFFu;
+    __syncthreads();  // one wave: orders the fills before what follows
+
+    if (most > kThinCap) {
+        // some diff has more records here than a lane holds: diff after diff, the lanes sharing
+        // the records of one diff (no two of them touch the same element)
+        for (int t = 0; t < W; ++t) {
+            const int h = t / LD_WAVE, l = t % LD_WAVE;
+            const int32_t b = __shfl(SETS == 1 ? p0[0] : (h == 0 ? p0[0] : p0[SETS - 1]), l, LD_WAVE);
+            const int32_t c = __shfl(SETS == 1 ? cnt[0] : (h == 0 ? cnt[0] : cnt[SETS - 1]), l, LD_WAVE);
+            const int32_t* __restrict__ di = tb.idx[t];
+            const float* __restrict__ dv = tb.val[t];
+            for (int32_t q = lane; q < c; q += LD_WAVE) {
+                const int32_t e = di[b + q] - lo;
+                if (static_cast<uint32_t>(e) < static_cast<uint32_t>(len)) apply_record(tile, e, dv[b + q], lr);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    } else {
+        // The lane's records, fetched as whole 16-byte blocks of four (the index and value arrays
+        // of this path are 16-byte aligned): slot j holds record (p0 & ~3) + j; slots before p0 or
+        // past the lane's count are marked empty (a negative index). (Single 4-byte loads, one
+        // record per lane and instruction, pulled a cache line per lane and record from L2.) Both
+        // sets of diffs are requested before the first is worked on.
+        int32_t ri_[SETS][kThinSlots];
+        float rp_[SETS][kThinSlots];
+#pragma unroll
+        for (int h = 0; h < SETS; ++h) {
+            const int32_t k0 = p0[h] & ~3, sh = p0[h] - k0;
+#pragma unroll
+            for (int v = 0; v < kThinSlots / 4; ++v) {
+                ld_u32x4 qi = {0u, 0u, 0u, 0u};
+                ld_f32x4 qv = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (4 * v < slots) {  // wave-uniform
+                    if (4 * v < sh + cnt[h]) {
+                        qi = *reinterpret_cast<const ld_u32x4*>(ip[h] + k0 + 4 * v);
+                        qv = *reinterpret_cast<const ld_f32x4*>(vp[h] + k0 + 4 * v);
+                    }
+                }
+                const uint32_t ei[4] = {qi.x, qi.y, qi.z, qi.w};
+                const float ev[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int j = 4 * v + c;
+                    const int32_t e = static_cast<int32_t>(ei[c]) - lo;
+                    const bool have = j >= sh && j < sh + cnt[h] && static_cast<uint32_t>(e) < static_cast<uint32_t>(len);
+                    ri_[h][j] = have ? e : -1;  // ascending, in-range indices never fail the last test
+                    rp_[h][j] = ev[c];
+                }
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < SETS; ++h) {
+            const uint32_t t = static_cast<uint32_t>(h * LD_WAVE + lane);
+            const int32_t (&ri)[kThinSlots] = ri_[h];
+            const float (&rp)[kThinSlots] = rp_[h];
+            for (int q = lane; q < kBitWords; q += LD_WAVE) {
+                seen[q] = 0;
+                multi[q] = 0;
+            }
+            __builtin_amdgcn_wave_barrier();
+            // which elements do several diffs of this set touch?
+            uint32_t again = 0;
+#pragma unroll
+            for (int i = 0; i < kThinSlots; ++i) {
+                if (i < slots && ri[i] >= 0) {
+                    const uint32_t bit = 1u << (ri[i] & 31);
+                    if (atomicOr(&seen[ri[i] >> 5], bit) & bit) again |= 1u << i;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kThinSlots; ++i)
+                if ((again >> i) & 1u) atomicOr(&multi[ri[i] >> 5], 1u << (ri[i] & 31));
+            __builtin_amdgcn_wave_barrier();
+            // elements of one diff only: updated now; the others are held back
+            int32_t ce[kConfLane];
+            float cp[kConfLane];
+            int nc = 0;
+#pragma unroll
+            for (int q = 0; q < kConfLane; ++q) { ce[q] = 0; cp[q] = 0.0f; }
+#pragma unroll
+            for (int i = 0; i < kThinSlots; ++i) {
+                if (i < slots && ri[i] >= 0) {
+                    const float p = __fmul_rn(lr, rp[i]);   // rounded product: never fused
+                    if ((multi[ri[i] >> 5] >> (ri[i] & 31)) & 1u) {
+#pragma unroll
+                        for (int q = 0; q < kConfLane; ++q)
+                            if (nc == q) { ce[q] = ri[i]; cp[q] = p; }
+                        ++nc;
+                    } else {
+                        tile[ri[i]] = __fsub_rn(tile[ri[i]], p);
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (__ballot(nc > kConfLane)) {
+                // more held back than a lane keeps (heavily overlapping diffs): the lanes take turns in
+                // diff order, each applying what it holds back
+                uint64_t turn = __ballot(nc > 0);
+                while (turn) {
+                    const int l = __builtin_ctzll(turn);
+                    turn &= turn - 1;
+                    if (lane == l) {
+#pragma unroll
+                        for (int i = 0; i < kThinSlots; ++i) {
+                            if (i < slots && ri[i] >= 0 && ((multi[ri[i] >> 5] >> (ri[i] & 31)) & 1u))
+                                tile[ri[i]] = __fsub_rn(tile[ri[i]], __fmul_rn(lr, rp[i]));
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            } else {
+                uint32_t pend = (1u << nc) - 1u;
+                while (__ballot(pend != 0)) {
+#pragma unroll
+                    for (int q = 0; q < kConfLane; ++q)
+                        if ((pend >> q) & 1u) atomicMin(&owner[ce[q] & (kOwner - 1)], (t << 13) | static_cast<uint32_t>(ce[q]));
+                    __builtin_amdgcn_wave_barrier();
+                    uint32_t won = 0;
+#pragma unroll
+                    for (int q = 0; q < kConfLane; ++q) {
+                        if (((pend >> q) & 1u) && owner[ce[q] & (kOwner - 1)] == ((t << 13) | static_cast<uint32_t>(ce[q]))) {
+                            tile[ce[q]] = __fsub_rn(tile[ce[q]], cp[q]);
+                            won |= 1u << q;
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int q = 0; q < kConfLane; ++q)
+                        if ((won >> q) & 1u) owner[ce[q] & (kOwner - 1)] = 0xFFFFFFFFu;
+                    __builtin_amdgcn_wave_barrier();
+                    pend &= ~won;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+
+    __syncthreads();
+    if (full) {
+        ld_f32x4* dst = reinterpret_cast<ld_f32x4*>(w + lo64);
+#pragma unroll
+        for (int j = 0; j < kThinSub / 4 / LD_WAVE; ++j)
+            ld_nt_store(reinterpret_cast<const ld_f32x4*>(tile)[j * LD_WAVE + lane], dst + j * LD_WAVE + lane);
+    } else {
+        for (int32_t e = lane; e < len; e += LD_WAVE) w[lo64 + e] = tile[e];
+    }
+}
+
 __global__ __launch_bounds__(256) void k_merge_scatter(float* __restrict__ w,
                                                        const int32_t* __restrict__ idx,
                                                        const float* __restrict__ val, int32_t K,
@@ -215,11 +489,37 @@ int32_t sub_tiles(int64_t n) { return static_cast<int32_t>((n + kSub - 1) / kSub
 
 }  // namespace
 
-extern "C" size_t ld_merge_sparse_workspace(int64_t n, int32_t W, const int64_t* K) {
-    (void)K;
-    if (n <= 0 || W <= 0) return 256;
+namespace {
+
+// A group of `gw` diffs whose largest holds `most` records is "thin" when a diff brings at most ~16
+// records to a sub-tile and the group is long: it then runs a lane per diff (k_merge_thin).
+bool thin_group(int64_t n, int32_t gw, int64_t most) { return gw > 10 && most * kSub <= 16 * n; }
+
+size_t chunk_table_bytes(int64_t n, int32_t W) {
     const int64_t group = W < kSweepGroup ? W : kSweepGroup;
     return ld_round_up(static_cast<size_t>(group) * (static_cast<size_t>(chunks(n)) + 1) * 4, 256);
+}
+
+size_t sub_table_bytes(int64_t n, int32_t gw) {
+    return ld_round_up(static_cast<size_t>(gw) * (static_cast<size_t>((n + kThinSub - 1) / kThinSub) + 1) * 4, 256);
+}
+
+}  // namespace
+
+// The chunk table always; for thin groups (when K is given) the larger per-sub-tile table, without
+// which they run as ordinary sweeps.
+extern "C" size_t ld_merge_sparse_workspace(int64_t n, int32_t W, const int64_t* K) {
+    if (n <= 0 || W <= 0) return 256;
+    size_t need = chunk_table_bytes(n, W);
+    if (K && n <= INT32_MAX && W <= LD_MAX_WINDOW) {
+        for (int32_t g0 = 0; g0 < W; g0 += kSweepGroup) {
+            const int32_t gw = (W - g0) < kSweepGroup ? (W - g0) : kSweepGroup;
+            int64_t most = 0;
+            for (int32_t t = g0; t < g0 + gw; ++t) most = K[t] > most ? K[t] : most;
+            if (thin_group(n, gw, most) && sub_table_bytes(n, gw) > need) need = sub_table_bytes(n, gw);
+        }
+    }
+    return need;
 }
 
 namespace {
@@ -252,8 +552,7 @@ ld_status merge_sparse_impl(float* w, int64_t n, const int32_t* const* idx, cons
         return LD_OK;
     }
 
-    if (!workspace || !ld_aligned(workspace, 256) ||
-        workspace_bytes < ld_merge_sparse_workspace(n, W, K))
+    if (!workspace || !ld_aligned(workspace, 256) || workspace_bytes < chunk_table_bytes(n, W))
         return LD_ERR_WORKSPACE;
     const int32_t nsub = sub_tiles(n), nchunk = chunks(n);
     int32_t* ctab = static_cast<int32_t*>(workspace);
@@ -261,18 +560,30 @@ ld_status merge_sparse_impl(float* w, int64_t n, const int32_t* const* idx, cons
         const int32_t gw = (W - g0) < kSweepGroup ? (W - g0) : kSweepGroup;
         DiffTable tb = {};
         int64_t most = 0;
+        bool aligned16 = true;
         for (int32_t t = 0; t < kTableMax; ++t) {
             const bool live = t < gw;
             tb.idx[t] = live ? idx[g0 + t] : nullptr;
             tb.val[t] = live ? val[g0 + t] : nullptr;
             tb.K[t] = live ? static_cast<int32_t>(K[g0 + t]) : 0;
             if (live && K[g0 + t] > most) most = K[g0 + t];
+            if (live && !(ld_aligned(idx[g0 + t], 16) && ld_aligned(val[g0 + t], 16))) aligned16 = false;
+        }
+        const dim3 grid((nsub + 7) / 8 * 8), wave(LD_WAVE);
+        const bool thin = thin_group(n, gw, most);
+        if (thin && aligned16 && workspace_bytes >= sub_table_bytes(n, gw)) {  // a lane per diff (else: the sweep below)
+            const int32_t tsub = static_cast<int32_t>((n + kThinSub - 1) / kThinSub);
+            const dim3 tgrid((tsub + 7) / 8 * 8);
+            k_subtab<<<dim3(static_cast<uint32_t>(most / (256 * kSubtabPer) + 1), gw), dim3(256), 0, s>>>(tb, tsub, ctab);
+            if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
+            if (gw <= LD_WAVE) k_merge_thin<1><<<tgrid, wave, 0, s>>>(w, n, tsub, tb, gw, ctab, lr);
+            else k_merge_thin<2><<<tgrid, wave, 0, s>>>(w, n, tsub, tb, gw, ctab, lr);
+            if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
+            continue;
         }
         launch_chunks(tb, gw, n, nchunk, ctab, s);
         if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
-        const dim3 grid((nsub + 7) / 8 * 8), wave(LD_WAVE);
         // at most ~16 records per diff and sub-tile: one window per diff is plenty
-        const bool thin = gw > 10 && most * kSub <= 16 * n;
         if (gw <= LD_WAVE) {
             if (thin) k_merge_sweep<20, 1, 1><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
             else k_merge_sweep<10, 2, 1><<<grid, wave, 0, s>>>(w, n, nchunk, tb, gw, ctab, lr);
@@ -337,7 +648,7 @@ extern "C" ld_status ld_merge_sparse_static(float* w, int64_t n, const int32_t* 
                                             ld_stream stream) {
     const ld_status st = check_diff_args(w, n, idx, val, K, W);
     if (st != LD_OK) return st;
-    if (ld_merge_sparse_workspace(n, W, K) > LD_MERGE_STATIC_SCRATCH) return LD_ERR_WORKSPACE;
+    if (chunk_table_bytes(n, W) > LD_MERGE_STATIC_SCRATCH) return LD_ERR_WORKSPACE;
     if (W == 0 || n == 0) return LD_OK;
     void* ptr = nullptr;
     const ld_status sp = static_scratch(&ptr);

@@ -21,7 +21,7 @@ import sqlite3
 import sys
 
 OURS = ("k_main", "k_prep", "k_upload", "k_hist", "k_bin", "k_gather", "k_select", "k_emit", "k_full", "k_paths",
-        "k_chunks", "k_merge_", "k_sparse_adam", "k_combine_", "k_snapshot", "k_adam")
+        "k_chunks", "k_subtab", "k_merge_", "k_sparse_adam", "k_combine_", "k_snapshot", "k_adam")
 
 
 def _short(name: str) -> str:

@@ -312,6 +312,60 @@ def test_merge_ragged_and_dense_windows(n, W, dens):
         np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref), err_msg=f"strategy {strategy}")
 
 
+@pytest.mark.parametrize("case", ["random", "identical", "pairs", "clustered", "short_then_long"])
+def test_merge_thin_long_windows(case):
+    # Long windows of very sparse diffs run a lane per diff: every lane holds its diff's records for
+    # the wave's sub-tile, elements touched by several diffs are held back and applied in diff order.
+    #   random          a few elements shared by two or three diffs
+    #   identical       every diff records the same positions: every record is held back, more per
+    #                   lane than it keeps (the lanes take turns)
+    #   pairs           diffs 2j and 2j+1 share all positions, values far apart in magnitude
+    #   clustered       one diff puts 300 records into one sub-tile (more than a lane holds)
+    #   short_then_long 70 diffs (two sets of lanes), the first ones empty or tiny
+    # Each also with the minimum workspace (no per-sub-tile table: the ordinary sweep) - same bits.
+    n = 3_000_017
+    rs = np.random.RandomState({"random": 1, "identical": 2, "pairs": 3, "clustered": 4, "short_then_long": 5}[case])
+    w0 = (rs.standard_normal(n) * 0.02).astype(np.float32)
+    W, k = 100, 3000
+    idxs, vals = [], []
+    if case == "random":
+        for t in range(W):
+            idxs.append(np.sort(rs.choice(n, k, replace=False)).astype(np.int32))
+    elif case == "identical":
+        same = np.sort(rs.choice(n, k, replace=False)).astype(np.int32)
+        idxs = [same.copy() for _ in range(W)]
+    elif case == "pairs":
+        for t in range(0, W, 2):
+            i = np.sort(rs.choice(n, k, replace=False)).astype(np.int32)
+            idxs += [i, i.copy()]
+    elif case == "clustered":
+        for t in range(W):
+            i = rs.choice(n, k, replace=False)
+            if t == 37:
+                i[:300] = 16_384 + rs.choice(8192, 300, replace=False)   # sub-tile 2
+            idxs.append(np.unique(i).astype(np.int32))
+    else:
+        W = 70
+        for t in range(W):
+            kk = [0, 1, 2][t] if t < 3 else k
+            idxs.append(np.sort(rs.choice(n, kk, replace=False)).astype(np.int32))
+    for t, i in enumerate(idxs):
+        scale = 1.0 if case != "pairs" else (1e-4 if t % 2 else 10.0)
+        vals.append((rs.standard_normal(i.size) * scale).astype(np.float32))
+    ref = oracle.merge_sparse(w0, idxs, vals, 0.1)
+    gi, gv = [to_gpu(i) for i in idxs], [to_gpu(v) for v in vals]
+    K = [i.size for i in idxs]
+    full_ws = ld.ld_merge_sparse_workspace(n, K)
+    min_ws = int(ld.load().ld_merge_sparse_workspace(n, len(K), None))
+    assert full_ws > min_ws, "this window was meant to qualify for the per-sub-tile table"
+    for nbytes in (full_ws, min_ws):
+        w = to_gpu(w0)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        ld.ld_merge_sparse(w, gi, gv, 0.1, workspace=ws, strategy=ld.LD_MERGE_SWEEP)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(bits(w.cpu().numpy()), bits(ref), err_msg=f"{case}, workspace {nbytes}")
+
+
 def test_merge_uneven_diffs_across_many_chunks():
     # Record positions are looked up per 49152-element chunk from guesses that assume evenly
     # spread records; these diffs are anything but (dense runs between long gaps, everything
