@@ -192,7 +192,6 @@ __global__ __launch_bounds__(LD_WAVE) void k_combine_emit(int64_t n, int32_t nch
                                                           int32_t* __restrict__ out_idx,
                                                           float* __restrict__ out_val, int64_t out_cap) {
     __shared__ uint32_t bm[kWords];      // recorded positions of the sub-tile
-    __shared__ uint32_t multi[kWords];   // ... those recorded by more than one list
     __shared__ uint16_t wpre[kWords];    // recorded positions before each bitmap word
     __shared__ float acc[kCap];          // sums, at the rank of their position among the recorded ones
     __shared__ uint16_t accq[kCap];      // ... and the positions themselves
@@ -208,15 +207,11 @@ __global__ __launch_bounds__(LD_WAVE) void k_combine_emit(int64_t n, int32_t nch
     if (mine == 0) return;  // nothing recorded in this sub-tile
     const int64_t off = static_cast<int64_t>(goff[grp]) + before;
 #pragma unroll
-    for (int j = 0; j < kWords / LD_WAVE; ++j) {
-        bm[j * LD_WAVE + lane] = 0;
-        multi[j * LD_WAVE + lane] = 0;
-    }
+    for (int j = 0; j < kWords / LD_WAVE; ++j) bm[j * LD_WAVE + lane] = 0;
     __syncthreads();  // one wave: orders the fill before the marks
     sweep_records<false>(tb, W, ctab, nchunk, s.sub, s.lo, s.hi, lane, [&](int, int32_t i, float) {
         const uint32_t q = static_cast<uint32_t>(i - s.lo);
-        const uint32_t bit = 1u << (q & 31);
-        if (atomicOr(&bm[q >> 5], bit) & bit) atomicOr(&multi[q >> 5], bit);  // seen before: by another list
+        atomicOr(&bm[q >> 5], 1u << (q & 31));
     });
     __syncthreads();
     {  // lane l owns bitmap words 4l .. 4l+3
@@ -240,25 +235,12 @@ __global__ __launch_bounds__(LD_WAVE) void k_combine_emit(int64_t n, int32_t nch
 #pragma unroll
         for (int j = 0; j < kCap / LD_WAVE; ++j) acc[j * LD_WAVE + lane] = 0.0f;
         __syncthreads();
-        // A position that one list alone records (nearly all of them) takes its sum in one store,
-        // +0 + v; only the positions of several lists are read, added to and written back, list
-        // after list - the chain of dependent LDS round trips that this pass would otherwise pay
-        // for every window of every list.
         sweep_records<true>(tb, W, ctab, nchunk, s.sub, s.lo, s.hi, lane, [&](int, int32_t i, float v) {
             const uint32_t q = static_cast<uint32_t>(i - s.lo);
-            const uint32_t bit = 1u << (q & 31);
-            const uint32_t rank = wpre[q >> 5] + __popc(bm[q >> 5] & (bit - 1u));
-            const bool shared = (multi[q >> 5] & bit) != 0;
-            const bool here = rank - r0 < static_cast<uint32_t>(kCap);
-            if (here && !shared) {
-                acc[rank - r0] = __fadd_rn(0.0f, v);
+            const uint32_t rank = wpre[q >> 5] + __popc(bm[q >> 5] & ((1u << (q & 31)) - 1u));
+            if (rank - r0 < static_cast<uint32_t>(kCap)) {
+                acc[rank - r0] = __fadd_rn(acc[rank - r0], v);
                 accq[rank - r0] = static_cast<uint16_t>(q);
-            }
-            if (__ballot(here && shared)) {
-                if (here && shared) {
-                    acc[rank - r0] = __fadd_rn(acc[rank - r0], v);
-                    accq[rank - r0] = static_cast<uint16_t>(q);
-                }
             }
         });
         __syncthreads();
