@@ -394,6 +394,35 @@ class DenseLeg:
         return 2 * self.n * self.W
 
 
+class MergeOnlyLeg:
+    """The window merge of a sparse workload on its own, for profiling runs: W random ascending index
+    lists of (up to) K records each with values of the workload's scale, no compress calls."""
+
+    def __init__(self, wl, dev):
+        self.wl, self.dev, self.n, self.W = wl, dev, wl.n, wl.window
+        K = int(wl.seg_k.astype(np.int64).sum())
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        self.idx, self.val = [], []
+        for _ in range(self.W):
+            i = torch.unique_consecutive(torch.sort(torch.randint(0, self.n, (K,), device=dev, generator=gen)).values)
+            self.idx.append(i.to(torch.int32))
+            self.val.append(torch.randn(i.numel(), device=dev, generator=gen) * wl.scale)
+        self.records = sum(t.numel() for t in self.idx)
+        self.w = torch.randn(self.n, device=dev, generator=gen) * wl.w_std
+        self.ws = torch.empty(ld.ld_merge_sparse_workspace(self.n, [t.numel() for t in self.idx]), dtype=torch.uint8,
+                              device=dev)
+        log(f"[mergeonly] {wl.name}: n={self.n:,} W={self.W} records={self.records:,}")
+
+    def step(self, tm):
+        tok = tm.start("merge_only")
+        ld.ld_merge_sparse(self.w, self.idx, self.val, self.wl.lr, self.ws)
+        tm.stop(tok)
+
+    def bytes_merge(self):
+        return 8 * self.n + 8 * self.records
+
+
 class CopyCal:
     """A plain copy of known size (1 GiB in, 1 GiB out) through ld_snapshot_layer: the yardstick the
     FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by."""
@@ -654,7 +683,8 @@ def main():
     ap.add_argument("--sparse", default="gpt2xl")
     ap.add_argument("--dense", default="llama7b")
     ap.add_argument("--legs", default="sparse,dense",
-                    help="comma list of sparse, dense, copycal (copycal: a 1 GiB plain copy, for counter calibration)")
+                    help="comma list of sparse, dense, mergeonly, copycal (mergeonly: the sparse workload's window merge "
+                         "alone, on random diffs; copycal: a 1 GiB plain copy, for counter calibration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true", help="skip the calls measured outside the step")
     ap.add_argument("--no-verify", action="store_true", help="skip the check of the outputs (profiling runs)")
@@ -672,6 +702,7 @@ def main():
     sparse = SparseLeg(synth.workload(args.sparse), dev, args.pool) if "sparse" in legs else None
     dense = DenseLeg(synth.workload(args.dense), dev) if "dense" in legs else None
     copycal = CopyCal(dev) if "copycal" in legs else None
+    mergeonly = MergeOnlyLeg(synth.workload(args.sparse), dev) if "mergeonly" in legs else None
     torch.cuda.synchronize()
     log(f"[setup] {time.perf_counter() - t_setup:.1f} s, {torch.cuda.memory_allocated() / 1e9:.1f} GB resident")
 
@@ -682,6 +713,8 @@ def main():
             dense.step(tm)
         if copycal:
             copycal.step(tm)
+        if mergeonly:
+            mergeonly.step(tm)
 
     for i in range(args.warmup):
         one_step(Timer())
@@ -746,17 +779,31 @@ def main():
         share["ld_merge_dense_adam"] = per["adam"]
     if copycal:
         calls["copycal(ld_snapshot_layer, 1 GiB)"] = roof("copycal", 4 * copycal.n)
+    if mergeonly:
+        calls["ld_merge_sparse(random window)"] = roof("merge_only", mergeonly.bytes_merge())
     next_rows = {}
     if sparse and not args.no_next_rows:
         ms = sparse.time_sparse_adam()
         log(f"[next row] ld_merge_sparse_adam: {ms:.2f} ms per call (W={sparse.W})")
         tf = sparse.flops_sparse_adam() / (ms * 1e-3) / 1e12
+        # vector ALU ceilings of the chip: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-operations/s.
+        # Plain fp32 FMA: 2 flops per lane-operation = 78.6 TFLOP/s (the published 157.3 counts packed
+        # two-wide FMA, which this build does not emit). Issue model of one Adam step on one element:
+        # 12 vector instructions, 2 of them (sqrt, rcp) quarter-rate: 18 issue slots if those do not overlap
+        # with full-rate issue, 12 if they overlap completely.
+        lane_ops = 256 * 4 * 16 * 2.4e9
+        steps = sparse.n * sparse.W
         next_rows["ld_merge_sparse_adam"] = {
             "ms": ms, "algorithmic_bytes": sparse.bytes_sparse_adam(),
             "hbm_GBps": sparse.bytes_sparse_adam() / (ms * 1e-3) / 1e9,
             "hbm_frac": sparse.bytes_sparse_adam() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "roofline": {"bound": "alu", "achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
-                         "note": "14 flops per element and step; peak = fp32 vector rate with packed FMA"},
+            "roofline": {"bound": "alu", "achieved": tf, "peak": 78.6, "unit": "TFLOP/s", "frac": tf / 78.6,
+                         "peak_packed_fma": 157.3, "frac_of_packed_peak": tf / 157.3,
+                         "issue_model_ms": {"18_slots_no_overlap": 18 * steps / lane_ops * 1e3,
+                                            "12_slots_full_overlap": 12 * steps / lane_ops * 1e3},
+                         "note": "14 flops per element and step; peak = plain (non-packed) fp32 FMA rate of the vector "
+                                 "ALUs, 256 CUs x 4 SIMDs x 16 lanes x 2 x 2.4 GHz; the measured time lies between the "
+                                 "two issue models: quarter-rate sqrt / rcp overlap partly with full-rate issue"},
             "note": "same gpt2xl window replayed through Adam on (w, m, v); not part of `value`"}
         ms, k_in, k_out = sparse.time_combine()
         log(f"[next row] ld_combine_sparse: {ms:.3f} ms per call (8 lists, {k_in:,} records -> {k_out:,})")

@@ -137,7 +137,8 @@ def _draw(dist: str, count: int, gen: torch.Generator, device, scale: float) -> 
         x = -scale * torch.sign(u) * torch.log1p(-2.0 * u.abs())
     elif dist == "student3":
         z = torch.randn(count, generator=gen, device=device, dtype=wide)
-        c = torch.randn(3, count, generator=gen, device=device, dtype=wide).square_().sum(0)
+        c = torch.randn(3, count, generator=gen, device=device, dtype=wide).square_()
+        c = (c[0] + c[1]) + c[2]  # elementwise adds (a reduction kernel over three rows gains nothing)
         x = scale * z / torch.sqrt(c / 3.0).clamp_min(1e-30)
     else:
         raise KeyError(dist)
