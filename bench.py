@@ -107,7 +107,7 @@ class SparseLeg:
         self.w = synth.base_weights(self.n, device=dev, std=wl.w_std)
         self.idx = [torch.empty(self.K, dtype=torch.int32, device=dev) for _ in range(self.W)]
         self.val = [torch.empty(self.K, dtype=torch.float32, device=dev) for _ in range(self.W)]
-        self.ws_c = torch.empty(ld.ld_compress_topk_workspace(self.off), dtype=torch.uint8, device=dev)
+        self.ws_c = torch.empty(ld.ld_compress_topk_workspace(self.off, self.k), dtype=torch.uint8, device=dev)
         self.ws_m = torch.empty(ld.ld_merge_sparse_workspace(self.n, [self.K] * self.W), dtype=torch.uint8,
                                 device=dev)
         self.it = 0

@@ -98,7 +98,7 @@ const char* ld_status_string(ld_status s);
  *   workspace  dev, 256-byte aligned, at least ld_compress_topk_workspace()
  *              bytes; contents on entry are irrelevant, contents on exit are
  *              unspecified. That minimum serves densities seg_k[s]/n_s up to
- *              about 3 % at full speed; the results are the same at any
+ *              about 1 % at full speed; the results are the same at any
  *              density, but denser calls run faster with the
  *              ld_compress_topk_workspace_for() size of their seg_k (the call
  *              uses as much of a larger workspace as its densities ask for)

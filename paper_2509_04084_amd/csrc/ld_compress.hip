@@ -67,8 +67,11 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / LD_WAVE;
 constexpr int kTile = 4096;                       // elements per k_main workgroup
-constexpr int kSlotMin = 256;                     // candidate slots per tile: 256 (6.25 % of a tile) serves
-constexpr int kSlotMax = 2048;                    // densities up to ~3 %; denser calls get more (multiples of 64)
+#ifndef LD_SLOT_MIN
+#define LD_SLOT_MIN 128
+#endif
+constexpr int kSlotMin = LD_SLOT_MIN;             // candidate slots per tile: 128 serve densities up to ~1 % (a denser
+constexpr int kSlotMax = 2048;                    // layout of the slots made the candidate passes slower); denser calls get more (multiples of 64)
 constexpr int kTilesPerGroup = 64;
 constexpr int kGroup = kTile * kTilesPerGroup;    // 262144 elements per small-pass workgroup
 constexpr int kBins = 2048;
