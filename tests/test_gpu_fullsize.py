@@ -52,6 +52,19 @@ def test_gpt2xl_compress_and_merge_full_size():
         torch.cuda.synchronize()
         idxs.append(idx)
         vals.append(val)
+        if t == 1:
+            # the same call by the full-segment strategy (every segment through the one-launch radix
+            # select: 5942 listed groups on a grid of at most 1024 workgroups, five phases handed over
+            # at its grid barrier): same records, same residual, and it did not give up waiting
+            r_full = r_before.clone()
+            idx_f, val_f = ld.ld_compress_topk(g, r_full, off, k, workspace=ws, strategy=ld.LD_COMPRESS_FULL)
+            paths, _ = ld.ld_compress_topk_paths(ws, off)
+            torch.cuda.synchronize()
+            assert torch.equal(idx_f, idx) and torch.equal(val_f.view(torch.int32), val.view(torch.int32))
+            assert torch.equal(r_full.view(torch.int32), r.view(torch.int32))
+            p = paths.cpu().numpy()
+            assert not np.any(p & 0x10000) and np.all((p & 0xFF) == ld.LD_PATH_FULL)
+            del r_full, idx_f, val_f
         # --- whole-output properties
         assert idx.numel() == K and val.numel() == K
         i64 = idx.to(torch.int64)
