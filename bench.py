@@ -423,6 +423,36 @@ class MergeOnlyLeg:
         return 8 * self.n + 8 * self.records
 
 
+class CombineOnlyLeg:
+    """ld_combine_sparse on its own, for profiling runs: `workers` random ascending lists of (up to) K
+    records each, as many workers' top-k lists of the sparse workload's shape and density."""
+
+    def __init__(self, wl, dev, workers=8):
+        self.n, self.workers = wl.n, workers
+        K = int(wl.seg_k.astype(np.int64).sum())
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(11)
+        self.idx, self.val = [], []
+        for _ in range(workers):
+            i = torch.unique_consecutive(torch.sort(torch.randint(0, self.n, (K,), device=dev, generator=gen)).values)
+            self.idx.append(i.to(torch.int32))
+            self.val.append(torch.randn(i.numel(), device=dev, generator=gen) * wl.scale)
+        self.records = sum(t.numel() for t in self.idx)
+        self.out_i = torch.empty(self.records, dtype=torch.int32, device=dev)
+        self.out_v = torch.empty(self.records, dtype=torch.float32, device=dev)
+        self.cnt = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.ws = torch.empty(ld.ld_combine_sparse_workspace(self.n, workers), dtype=torch.uint8, device=dev)
+        log(f"[combineonly] {wl.name}: n={self.n:,} lists={workers} records={self.records:,}")
+
+    def step(self, tm):
+        tok = tm.start("combine_only")
+        ld.ld_combine_sparse(self.idx, self.val, self.n, 1.0 / self.workers, self.out_i, self.out_v, self.cnt, self.ws)
+        tm.stop(tok)
+
+    def bytes_combine(self):
+        return 8 * (self.records + int(self.cnt.item()))
+
+
 class CopyCal:
     """A plain copy of known size (1 GiB in, 1 GiB out) through ld_snapshot_layer: the yardstick the
     FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by."""
@@ -683,8 +713,9 @@ def main():
     ap.add_argument("--sparse", default="gpt2xl")
     ap.add_argument("--dense", default="llama7b")
     ap.add_argument("--legs", default="sparse,dense",
-                    help="comma list of sparse, dense, mergeonly, copycal (mergeonly: the sparse workload's window merge "
-                         "alone, on random diffs; copycal: a 1 GiB plain copy, for counter calibration)")
+                    help="comma list of sparse, dense, mergeonly, combineonly, copycal (mergeonly: the sparse workload's "
+                         "window merge alone, on random diffs; combineonly: ld_combine_sparse alone, on 8 random lists; "
+                         "copycal: a 1 GiB plain copy, for counter calibration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true", help="skip the calls measured outside the step")
     ap.add_argument("--no-verify", action="store_true", help="skip the check of the outputs (profiling runs)")
@@ -703,6 +734,7 @@ def main():
     dense = DenseLeg(synth.workload(args.dense), dev) if "dense" in legs else None
     copycal = CopyCal(dev) if "copycal" in legs else None
     mergeonly = MergeOnlyLeg(synth.workload(args.sparse), dev) if "mergeonly" in legs else None
+    combineonly = CombineOnlyLeg(synth.workload(args.sparse), dev) if "combineonly" in legs else None
     torch.cuda.synchronize()
     log(f"[setup] {time.perf_counter() - t_setup:.1f} s, {torch.cuda.memory_allocated() / 1e9:.1f} GB resident")
 
@@ -715,6 +747,8 @@ def main():
             copycal.step(tm)
         if mergeonly:
             mergeonly.step(tm)
+        if combineonly:
+            combineonly.step(tm)
 
     for i in range(args.warmup):
         one_step(Timer())
@@ -781,6 +815,8 @@ def main():
         calls["copycal(ld_snapshot_layer, 1 GiB)"] = roof("copycal", 4 * copycal.n)
     if mergeonly:
         calls["ld_merge_sparse(random window)"] = roof("merge_only", mergeonly.bytes_merge())
+    if combineonly:
+        calls["ld_combine_sparse(random lists)"] = roof("combine_only", combineonly.bytes_combine())
     next_rows = {}
     if sparse and not args.no_next_rows:
         ms = sparse.time_sparse_adam()
