@@ -41,6 +41,19 @@ __device__ __forceinline__ void apply_record(float* tile, int32_t local, float v
     tile[local] = __fsub_rn(tile[local], p);
 }
 
+// N records per lane of ONE diff (so no two of the wave's 64 N records name the same element):
+// those inside [lo, hi) are all read before any is written - one round trip to LDS instead of N.
+template <int N>
+__device__ __forceinline__ void apply_records(float* tile, const int32_t (&i)[N], const float (&v)[N], int32_t lo,
+                                              int32_t hi, float lr) {
+    float cur[N];
+#pragma unroll
+    for (int u = 0; u < N; ++u) cur[u] = (i[u] >= lo && i[u] < hi) ? tile[i[u] - lo] : 0.0f;
+#pragma unroll
+    for (int u = 0; u < N; ++u)
+        if (i[u] >= lo && i[u] < hi) tile[i[u] - lo] = __fsub_rn(cur[u], __fmul_rn(lr, v[u]));   // rounded product: never fused
+}
+
 // Applies the records of one diff at positions [p, end) that fall into [lo, hi), up to the
 // first record at or beyond hi. kDeep loads of 64 records are in flight together: a dense
 // diff has many such batches per sub-tile, and one at a time would leave the wave waiting
@@ -60,9 +73,7 @@ __device__ __forceinline__ void apply_from(float* tile, const int32_t* __restric
             i[u] = have ? idx[q] : INT_MAX;
             v[u] = have ? val[q] : 0.0f;
         }
-#pragma unroll
-        for (int u = 0; u < kDeep; ++u)
-            if (i[u] >= lo && i[u] < hi) apply_record(tile, i[u] - lo, v[u], lr);
+        apply_records(tile, i, v, lo, hi, lr);
         if (__ballot(i[kDeep - 1] >= hi)) break;
     }
 }
@@ -169,15 +180,11 @@ __global__ __launch_bounds__(LD_WAVE) void k_merge_sweep(float* __restrict__ w, 
                 const int t = t0 + g;
                 const int32_t first = __builtin_amdgcn_readfirstlane(A.ri[g][0]);
                 if (A.s[g] == A.b[g] || first <= lo) {
-                    // the window begins before the sub-tile's records do
-                    bool more = true;
-#pragma unroll
-                    for (int u = 0; u < WIN; ++u) {
-                        if (more) {
-                            if (A.ri[g][u] >= lo && A.ri[g][u] < hi) apply_record(tile, A.ri[g][u] - lo, A.rv[g][u], lr);
-                            more = !__ballot(A.ri[g][u] >= hi);
-                        }
-                    }
+                    // the window begins before the sub-tile's records do; ascending indices: a record
+                    // at or beyond hi (or the padding past the chunk's end) in the last window says
+                    // that nothing of this sub-tile follows
+                    apply_records(tile, A.ri[g], A.rv[g], lo, hi, lr);
+                    const bool more = !__ballot(A.ri[g][WIN - 1] >= hi);
                     if (more) apply_from(tile, tb.idx[t], tb.val[t], A.s[g] + WIN * LD_WAVE, A.e[g], lo, hi, lr, lane);
                 } else {
                     // guess too late: find the first record of the sub-tile inside the chunk
