@@ -382,7 +382,8 @@ ld_status ld_merge_sparse_adam(float* w, float* m, float* v, int64_t n,
  *              (sum K always suffices)
  *   out_count  dev int64, 8-byte aligned: the number of distinct indices (compare
  *              with out_cap to detect a truncated output)
- *   workspace  dev, 256-byte aligned, ld_combine_sparse_workspace() bytes
+ *   workspace  dev, 256-byte aligned, ld_combine_sparse_workspace() bytes (about
+ *              n / 8: a bit per index, plus small tables)
  * Errors: LD_ERR_NULL, LD_ERR_RANGE, LD_ERR_ALIGN, LD_ERR_WORKSPACE, LD_ERR_HIP.
  */
 #define LD_MAX_WORKERS 64

@@ -7,20 +7,21 @@
 // and multiplied by `scale` (1 for a sum, 1/N for a mean).
 //
 // The index space is cut into 8192-element sub-tiles, one wave each, in two passes:
-//   k_combine_count  marks the sub-tile's recorded positions in an LDS bitmap and
-//                    counts them;
+//   k_combine_count  marks the sub-tile's recorded positions in an LDS bitmap, counts
+//                    them and leaves the bitmap in the workspace (1 KB per sub-tile);
 //   k_combine_groups / k_combine_scan   scan the counts (inside groups of 1024
 //                    sub-tiles, then the at most 1024 group sums);
-//   k_combine_emit   rebuilds the bitmap, ranks every position among the recorded
-//                    ones and adds the values at their rank in a small LDS array, list
+//   k_combine_emit   fetches the bitmap (marking the positions a second time cost more
+//                    than the n / 8 bytes written and read), ranks every position among the
+//                    recorded ones and adds the values at their rank in a small LDS array, list
 //                    after list (LDS operations of one wave complete in order, and
 //                    inside one list the indices are distinct), then writes the array
 //                    out as one contiguous run at the sub-tile's offset. A dense tile
 //                    of the sub-tile would cost 32 KB of LDS per wave and leave one
 //                    wave per SIMD; the ranked array takes 7.5 KB.
 // The records of a sub-tile are found as in ld_merge_sparse: chunk table +
-// interpolated 128-record windows, verified. HBM traffic: the records twice (a third
-// reading comes from L2), the output once.
+// interpolated 128-record windows, verified. HBM traffic: the indices twice, the values
+// once, the bitmaps out and in, the output once.
 #include "ld_sparse_common.h"
 
 namespace {
@@ -121,7 +122,8 @@ __device__ __forceinline__ SubTile sub_tile(int64_t n) {
 
 __global__ __launch_bounds__(LD_WAVE) void k_combine_count(int64_t n, int32_t nchunk, DiffTable tb, int32_t W,
                                                            const int32_t* __restrict__ ctab,
-                                                           uint32_t* __restrict__ counts) {
+                                                           uint32_t* __restrict__ counts,
+                                                           uint32_t* __restrict__ bitmaps) {
     __shared__ uint32_t bm[kWords];
     const int lane = threadIdx.x;
     const SubTile s = sub_tile(n);
@@ -136,7 +138,11 @@ __global__ __launch_bounds__(LD_WAVE) void k_combine_count(int64_t n, int32_t nc
     __syncthreads();
     uint32_t c = 0;
 #pragma unroll
-    for (int j = 0; j < kWords / LD_WAVE; ++j) c += __popc(bm[j * LD_WAVE + lane]);
+    for (int j = 0; j < kWords / LD_WAVE; ++j) {
+        const uint32_t word = bm[j * LD_WAVE + lane];
+        c += __popc(word);
+        bitmaps[s.sub * kWords + j * LD_WAVE + lane] = word;  // k_combine_emit takes it from here
+    }
     c = ld_wave_sum(c);
     if (lane == 0) counts[s.sub] = c;
 }
@@ -188,7 +194,8 @@ __global__ __launch_bounds__(LD_WAVE) void k_combine_emit(int64_t n, int32_t nch
                                                           const int32_t* __restrict__ ctab,
                                                           const uint32_t* __restrict__ prefix, int32_t nsub,
                                                           const uint32_t* __restrict__ gsum,
-                                                          const uint32_t* __restrict__ goff, float scale,
+                                                          const uint32_t* __restrict__ goff,
+                                                          const uint32_t* __restrict__ bitmaps, float scale,
                                                           int32_t* __restrict__ out_idx,
                                                           float* __restrict__ out_val, int64_t out_cap) {
     __shared__ uint32_t bm[kWords];      // recorded positions of the sub-tile
@@ -207,13 +214,8 @@ __global__ __launch_bounds__(LD_WAVE) void k_combine_emit(int64_t n, int32_t nch
     if (mine == 0) return;  // nothing recorded in this sub-tile
     const int64_t off = static_cast<int64_t>(goff[grp]) + before;
 #pragma unroll
-    for (int j = 0; j < kWords / LD_WAVE; ++j) bm[j * LD_WAVE + lane] = 0;
-    __syncthreads();  // one wave: orders the fill before the marks
-    sweep_records<false>(tb, W, ctab, nchunk, s.sub, s.lo, s.hi, lane, [&](int, int32_t i, float) {
-        const uint32_t q = static_cast<uint32_t>(i - s.lo);
-        atomicOr(&bm[q >> 5], 1u << (q & 31));
-    });
-    __syncthreads();
+    for (int j = 0; j < kWords / LD_WAVE; ++j) bm[j * LD_WAVE + lane] = bitmaps[s.sub * kWords + j * LD_WAVE + lane];
+    __syncthreads();  // one wave: orders the fill before what reads it
     {  // lane l owns bitmap words 4l .. 4l+3
         uint32_t c[kWords / LD_WAVE], sum = 0;
 #pragma unroll
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(LD_WAVE) void k_combine_emit(int64_t n, int32_t nch
 }  // namespace
 
 namespace {
-struct CombineLayout { size_t ctab, counts, gsum, goff, total; };
+struct CombineLayout { size_t ctab, counts, gsum, goff, bitmaps, total; };
 CombineLayout combine_layout(int64_t n, int32_t N) {
     CombineLayout L;
     size_t o = 0;
@@ -270,6 +272,7 @@ CombineLayout combine_layout(int64_t n, int32_t N) {
     L.counts = take(nsub * 4);
     L.gsum = take(ngrp * 4);
     L.goff = take(ngrp * 4);
+    L.bitmaps = take(nsub * kWords * 4);  // recorded positions of every sub-tile: n / 8 bytes
     L.total = o;
     return L;
 }
@@ -313,6 +316,7 @@ extern "C" ld_status ld_combine_sparse(const int32_t* const* idx, const float* c
     uint32_t* counts = reinterpret_cast<uint32_t*>(ws + L.counts);
     uint32_t* gsum = reinterpret_cast<uint32_t*>(ws + L.gsum);
     uint32_t* goff = reinterpret_cast<uint32_t*>(ws + L.goff);
+    uint32_t* bitmaps = reinterpret_cast<uint32_t*>(ws + L.bitmaps);
     static_assert(LD_MAX_WORKERS <= kGroupMax, "one launch must hold every list");
     DiffTable tb = {};
     for (int32_t t = 0; t < kGroupMax; ++t) {
@@ -325,13 +329,14 @@ extern "C" ld_status ld_combine_sparse(const int32_t* const* idx, const float* c
     const dim3 grid(static_cast<uint32_t>((nsub + 7) / 8 * 8)), wave(LD_WAVE);
     launch_chunks(tb, N, n, nchunk, ctab, s);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
-    k_combine_count<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts);
+    k_combine_count<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts, bitmaps);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     k_combine_groups<<<dim3(ngrp), dim3(256), 0, s>>>(counts, nsub, gsum);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
     k_combine_scan<<<dim3(1), dim3(1024), 0, s>>>(gsum, goff, ngrp, out_count);
     if (ld_launch_status() != LD_OK) return LD_ERR_HIP;
-    k_combine_emit<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts, nsub, gsum, goff, scale, out_idx, out_val,
+    k_combine_emit<<<grid, wave, 0, s>>>(n, nchunk, tb, N, ctab, counts, nsub, gsum, goff, bitmaps, scale, out_idx,
+                                         out_val,
                                          out_cap);
     return ld_launch_status();
 }
