@@ -1434,8 +1434,9 @@ __global__ __launch_bounds__(kThreads) void k_emit(float* __restrict__ r, int32_
             const uint32_t cnt = static_cast<uint32_t>(__shfl(static_cast<int>(rank), row * ROW + ROW - 1, LD_WAVE));
             const int64_t o0 = gr.out0 + tile_out[tl0 + kTiles * q + row];
             for (uint32_t i = lane; i < cnt; i += LD_WAVE) {
-                out_idx[o0 + i] = stage_i[w][row * kFast + i];
-                out_val[o0 + i] = stage_v[w][row * kFast + i];
+                // streamed past the caches: the records are read much later, by another call
+                __builtin_nontemporal_store(stage_i[w][row * kFast + i], out_idx + o0 + i);
+                __builtin_nontemporal_store(stage_v[w][row * kFast + i], out_val + o0 + i);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
